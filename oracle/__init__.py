@@ -1,0 +1,133 @@
+"""Python face of the CPU oracle (``oracle/flash3d_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the benchmark's
+cpu-baseline leg. The product package never imports this module and this module never imports
+the product package. Arguments are numpy arrays; marshalling only, no arithmetic of the method.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Dict, Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "flash3d_oracle.c")
+_LIB = os.path.join(_HERE, "libf3d_oracle.so")
+
+HASHES = {"xor_mod": 0, "xor_div": 1, "zorder_mod": 2, "zorder_div": 3}
+MODES = {"plain": 0, "shift": 1, "stride": 2}
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fast-math, no FMA contraction, OpenMP for the attention loops)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-fPIC", "-shared",
+               _SRC, "-o", _LIB, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.orc_morton3.restype = ctypes.c_uint64
+        _lib.orc_morton3.argtypes = [ctypes.c_uint32] * 3
+        _lib.orc_hash.restype = ctypes.c_int64
+        _lib.orc_bucketize.restype = ctypes.c_int64
+        _lib.orc_group_of_bucket.restype = ctypes.c_int64
+        _lib.orc_group_of_bucket.argtypes = [ctypes.c_int64] + [ctypes.c_int32] * 4
+        _lib.orc_attn.restype = ctypes.c_int64
+        _lib.orc_unpermute.restype = ctypes.c_int
+        _lib.orc_max_threads.restype = ctypes.c_int
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def morton3(x: int, y: int, z: int) -> int:
+    return int(lib().orc_morton3(x, y, z))
+
+
+def hash_bucket(hash_name: str, K: int, vmax, v, div: int = 0):
+    """Bucket of voxel v for a scan with K buckets and per-axis voxel maximum vmax.
+    Returns (bucket, divisor, probe_step)."""
+    vm = np.asarray(vmax, dtype=np.int32)
+    vv = np.asarray(v, dtype=np.int32)
+    d = ctypes.c_int64(0)
+    s = ctypes.c_int32(0)
+    h = lib().orc_hash(ctypes.c_int32(HASHES[hash_name]), ctypes.c_int64(K), _p(vm), ctypes.c_int32(div), _p(vv),
+                       ctypes.byref(d), ctypes.byref(s))
+    return int(h), int(d.value), int(s.value)
+
+
+def group_of_bucket(j: int, m: int, mode: str, shift: int = 2, stride: int = 2) -> int:
+    return int(lib().orc_group_of_bucket(j, m, MODES[mode], shift, stride))
+
+
+def bucketize(coords: np.ndarray, batch_offsets: np.ndarray, voxel_size: float, bucket_size: int,
+              hash_name: str = "zorder_div", n_probes: int = 6, div: int = 0, probe_step: int = 0) -> Dict[str, np.ndarray]:
+    """Algorithms 1+2 under the round-synchronous, index-ordered schedule. Returns a dict with
+    bucket_id, bucket_off, round_of, perm, inv_perm, offsets[K+1], scan_bucket_start[n_scans+1]."""
+    coords = np.ascontiguousarray(coords, dtype=np.float32).reshape(-1, 3)
+    bo = np.ascontiguousarray(batch_offsets, dtype=np.int32)
+    n, n_scans = coords.shape[0], bo.shape[0] - 1
+    kmax = n // max(bucket_size, 1) + n_scans + 1
+    out = {k: np.full(n, -1, dtype=np.int32) for k in ("bucket_id", "bucket_off", "round_of", "perm", "inv_perm")}
+    offsets = np.zeros(kmax + 1, dtype=np.int32)
+    sbs = np.zeros(n_scans + 1, dtype=np.int32)
+    K = lib().orc_bucketize(_p(coords), _p(bo), ctypes.c_int64(n), ctypes.c_int32(n_scans),
+                            ctypes.c_float(voxel_size), ctypes.c_int32(bucket_size), ctypes.c_int32(HASHES[hash_name]),
+                            ctypes.c_int32(n_probes), ctypes.c_int32(div), ctypes.c_int32(probe_step),
+                            _p(out["bucket_id"]), _p(out["bucket_off"]), _p(out["round_of"]), _p(out["perm"]),
+                            _p(out["inv_perm"]), _p(offsets), _p(sbs))
+    if K < 0:
+        raise ValueError("orc_bucketize: bad arguments")
+    out["offsets"] = offsets[: K + 1].copy()
+    out["scan_bucket_start"] = sbs
+    return out
+
+
+def attn(q: np.ndarray, k: np.ndarray, v: np.ndarray, perm: Optional[np.ndarray], offsets: np.ndarray,
+         scan_bucket_start: np.ndarray, scope_buckets: int, mode: str, heads: int, head_dim: int,
+         shift: int = 2, stride: int = 2, scale: Optional[float] = None, row_sel: Optional[np.ndarray] = None) -> np.ndarray:
+    """Scope-restricted multi-head self-attention in binary64. q,k,v: uint16 bf16 bit patterns
+    [n, heads*head_dim]. Returns float64 [n, heads*head_dim] in bucket-major row order (rows not
+    selected by row_sel are NaN)."""
+    q, k, v = (np.ascontiguousarray(a, dtype=np.uint16) for a in (q, k, v))
+    n = q.shape[0]
+    off = np.ascontiguousarray(offsets, dtype=np.int32)
+    sbs = np.ascontiguousarray(scan_bucket_start, dtype=np.int32)
+    pm = None if perm is None else np.ascontiguousarray(perm, dtype=np.int32)
+    sel = None if row_sel is None else np.ascontiguousarray(row_sel, dtype=np.uint8)
+    out = np.full((n, heads * head_dim), np.nan, dtype=np.float64)
+    sc = (1.0 / np.sqrt(float(head_dim))) if scale is None else float(scale)
+    r = lib().orc_attn(_p(q), _p(k), _p(v), _p(pm), _p(off), _p(sbs), ctypes.c_int32(sbs.shape[0] - 1),
+                       ctypes.c_int32(scope_buckets), ctypes.c_int32(MODES[mode]), ctypes.c_int32(shift),
+                       ctypes.c_int32(stride), ctypes.c_int32(heads), ctypes.c_int32(head_dim), ctypes.c_double(sc),
+                       _p(sel), _p(out))
+    if r < 0:
+        raise ValueError("orc_attn: bad arguments")
+    return out
+
+
+def unpermute(src: np.ndarray, perm: np.ndarray) -> np.ndarray:
+    """dst[perm[p]] = src[p] for 2-D arrays of any dtype."""
+    src = np.ascontiguousarray(src)
+    pm = np.ascontiguousarray(perm, dtype=np.int32)
+    dst = np.zeros_like(src)
+    rb = src.strides[0]
+    lib().orc_unpermute(_p(src), _p(pm), ctypes.c_int64(src.shape[0]), ctypes.c_int64(rb), _p(dst))
+    return dst
+
+
+def max_threads() -> int:
+    return int(lib().orc_max_threads())

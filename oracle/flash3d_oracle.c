@@ -1,0 +1,380 @@
+/*
+ * CPU oracle for the PSH bucketize + Bucket-Swin attention path of Flash3D (arXiv 2412.16481).
+ *
+ * TEST INFRASTRUCTURE ONLY. This file is the slow, plain reference the HIP library is checked
+ * against. It shares no code with the HIP path and must never be linked into it or called from
+ * it; only the tests, the smoke check and the benchmark's cpu-baseline leg use it.
+ *
+ * What is defined here and where it comes from:
+ *   - voxel coordinate, the four hash functions          (Section 4.1, "Hash functions")
+ *   - bucket assignment with rebalancing                 (Algorithm 1 and Algorithm 2)
+ *   - scatter index bucket_base[bucket_id] + bucket_off  (Section 4.1, "Input and Output")
+ *   - scope regrouping: plain / shifted / strided        (Section 4.2, worked example; Table 2 caption)
+ *   - multi-head self-attention inside one scope         (Section 4.2; Appendix "Bucket-Swin")
+ *
+ * Algorithms 1 and 2 let hardware atomics decide the arrival order, so their result depends on
+ * the schedule. The oracle fixes one admissible schedule: all points take the same step together
+ * (first the direct hash of Algorithm 1, then probe 1 of Algorithm 2, then probe 2, ...), and
+ * inside a step the points contending for a bucket are served in increasing input index. Under
+ * that schedule the optimistic increment followed by a roll-back of Algorithm 2 leaves the same
+ * counters as "take the slot only if one is free", which is what the loops below do.
+ *
+ * Everything in the bucketing half is integer arithmetic except the voxel coordinate, which is
+ * three IEEE-754 binary32 operations (subtract, multiply, floor) evaluated one by one; build
+ * with -ffp-contract=off. The attention half is the plain definition in binary64.
+ *
+ * Parity pins (see tests/test_oracle_*.py): hand-computed hashes and Morton codes, the paper's
+ * regrouping example, a literal thread-by-thread simulation of Algorithms 1+2, stable-argsort on
+ * overflow-free inputs, brute-force masked dense attention, a library dense-attention routine on
+ * the single-scope case, closed forms and invariants. No function here is unpinned.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORC_XOR_MOD = 0, ORC_XOR_DIV = 1, ORC_ZORDER_MOD = 2, ORC_ZORDER_DIV = 3 };
+enum { ORC_PLAIN = 0, ORC_SHIFT = 1, ORC_STRIDE = 2 };
+
+#define ORC_VOXEL_MAX ((1 << 21) - 1) /* 21 bits per axis fit a 63-bit Morton code */
+
+/* ------------------------------------------------------------------ hash functions (Section 4.1) */
+
+/* Z-order code: bit k of x goes to bit 3k, of y to 3k+1, of z to 3k+2. */
+uint64_t orc_morton3(uint32_t x, uint32_t y, uint32_t z)
+{
+    uint64_t code = 0;
+    for (int k = 0; k < 21; ++k) {
+        code |= (uint64_t)((x >> k) & 1u) << (3 * k);
+        code |= (uint64_t)((y >> k) & 1u) << (3 * k + 1);
+        code |= (uint64_t)((z >> k) & 1u) << (3 * k + 2);
+    }
+    return code;
+}
+
+static int bit_width_u64(uint64_t v)
+{
+    int w = 0;
+    while (v) { ++w; v >>= 1; }
+    return w;
+}
+
+/* Per-scan hash setting: number of buckets K, divisor D, probe step, per-axis voxel maximum. */
+typedef struct {
+    int32_t hash;
+    int64_t K;
+    uint64_t D;
+    int32_t step;
+    int32_t vmax[3];
+} orc_hash_cfg;
+
+static uint64_t hash_code(const orc_hash_cfg *c, const int32_t v[3])
+{
+    if (c->hash == ORC_XOR_MOD || c->hash == ORC_XOR_DIV)
+        return (uint64_t)((uint32_t)v[0] ^ (uint32_t)v[1] ^ (uint32_t)v[2]);
+    return orc_morton3((uint32_t)v[0], (uint32_t)v[1], (uint32_t)v[2]);
+}
+
+static int64_t hash_bucket(const orc_hash_cfg *c, const int32_t v[3])
+{
+    uint64_t code = hash_code(c, v);
+    if (c->hash == ORC_XOR_MOD || c->hash == ORC_ZORDER_MOD)
+        return (int64_t)(code % (uint64_t)c->K);
+    uint64_t q = code / c->D;
+    return (int64_t)(q < (uint64_t)c->K ? q : (uint64_t)c->K - 1);
+}
+
+/* Fill divisor and probe step. div_override/step_override > 0 replace the automatic choice.
+ * Automatic divisor: the smallest D for which (largest possible code) / D < K.
+ * Automatic probe step: 1 voxel for the mod hashes; for the div hashes about the edge length of
+ * the cell of voxels that share one bucket. */
+static void hash_cfg_fill(orc_hash_cfg *c, int32_t hash, int64_t K, const int32_t vmax[3],
+                          int32_t div_override, int32_t step_override)
+{
+    c->hash = hash;
+    c->K = K;
+    memcpy(c->vmax, vmax, sizeof(c->vmax));
+    int32_t vm = vmax[0] > vmax[1] ? vmax[0] : vmax[1];
+    vm = vm > vmax[2] ? vm : vmax[2];
+    int nb = bit_width_u64((uint64_t)vm);
+    if (nb < 1) nb = 1;
+    uint64_t D = 1;
+    if (hash == ORC_XOR_DIV) D = (((uint64_t)1 << nb) - 1) / (uint64_t)K + 1;
+    if (hash == ORC_ZORDER_DIV) D = orc_morton3(vmax[0], vmax[1], vmax[2]) / (uint64_t)K + 1;
+    if (div_override > 0) D = (uint64_t)div_override;
+    c->D = D;
+    int64_t step = 1;
+    if (hash == ORC_XOR_DIV) step = (int64_t)(D > (uint64_t)ORC_VOXEL_MAX ? (uint64_t)ORC_VOXEL_MAX : D);
+    if (hash == ORC_ZORDER_DIV) step = (int64_t)1 << ((bit_width_u64(D) + 2) / 3);
+    if (step_override > 0) step = step_override;
+    c->step = (int32_t)step;
+}
+
+/* The probe offsets of Algorithm 2: the six axis neighbours at distance `step`, in this order. */
+static const int8_t ORC_PROBE_DIR[6][3] = {
+    {+1, 0, 0}, {-1, 0, 0}, {0, +1, 0}, {0, -1, 0}, {0, 0, +1}, {0, 0, -1}};
+
+/* Exposed for the tests: bucket of voxel v under a hash setting built from (K, vmax, overrides). */
+int64_t orc_hash(int32_t hash, int64_t K, const int32_t vmax[3], int32_t div_override,
+                 const int32_t v[3], int64_t *divisor_out, int32_t *step_out)
+{
+    orc_hash_cfg c;
+    hash_cfg_fill(&c, hash, K, vmax, div_override, 0);
+    if (divisor_out) *divisor_out = (int64_t)c.D;
+    if (step_out) *step_out = c.step;
+    return hash_bucket(&c, v);
+}
+
+/* ------------------------------------------------------------------ bucketize (Algorithms 1, 2) */
+
+/*
+ * coords        [n,3] binary32, scans stored back to back
+ * batch_offsets [n_scans+1], scan b owns points batch_offsets[b] .. batch_offsets[b+1]-1
+ * bucket_size   capacity S of one hash bucket
+ * outputs (caller allocates; any may be NULL except perm):
+ *   bucket_id[n]   global bucket index of point i          (Section 4.1 "Input and Output")
+ *   bucket_off[n]  slot of point i inside its bucket
+ *   round_of[n]    0 = direct hash, 1..n_probes = probe that placed it, n_probes+1 = recycled
+ *   perm[n]        perm[row] = input index stored at that row of the bucket-major array
+ *   inv_perm[n]    inv_perm[i] = bucket_base[bucket_id[i]] + bucket_off[i]
+ *   offsets[K+1]   first row of every bucket (exclusive scan of the final counters), K = total buckets
+ *   scan_bucket_start[n_scans+1]  first bucket of every scan
+ * returns the total number of buckets, or -1 on bad arguments.
+ */
+int64_t orc_bucketize(const float *coords, const int32_t *batch_offsets, int64_t n, int32_t n_scans,
+                      float voxel_size, int32_t bucket_size, int32_t hash, int32_t n_probes,
+                      int32_t div_override, int32_t step_override,
+                      int32_t *bucket_id, int32_t *bucket_off, int32_t *round_of,
+                      int32_t *perm, int32_t *inv_perm, int32_t *offsets, int32_t *scan_bucket_start)
+{
+    if (n < 0 || n_scans < 0 || !(voxel_size > 0.0f) || bucket_size <= 0 || hash < 0 || hash > 3 ||
+        n_probes < 0 || n_probes > 6 || !perm)
+        return -1;
+    const float inv = 1.0f / voxel_size;
+    int64_t kbase = 0; /* buckets of earlier scans */
+    int32_t *id = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+    int32_t *off = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+    if (offsets) offsets[0] = 0;
+
+    for (int32_t b = 0; b < n_scans; ++b) {
+        const int64_t p0 = batch_offsets[b], p1 = batch_offsets[b + 1];
+        const int64_t nb = p1 - p0;
+        if (scan_bucket_start) scan_bucket_start[b] = (int32_t)kbase;
+        if (nb <= 0) continue;
+        const int64_t K = (nb + bucket_size - 1) / bucket_size;
+
+        /* voxel coordinates: subtract the scan's minimum, scale, floor (Algorithm 1, line 4) */
+        float mn[3] = {coords[3 * p0], coords[3 * p0 + 1], coords[3 * p0 + 2]};
+        for (int64_t i = p0; i < p1; ++i)
+            for (int a = 0; a < 3; ++a)
+                if (coords[3 * i + a] < mn[a]) mn[a] = coords[3 * i + a];
+        int32_t *v = (int32_t *)malloc(sizeof(int32_t) * 3 * (size_t)nb);
+        int32_t vmax[3] = {0, 0, 0};
+        for (int64_t i = 0; i < nb; ++i)
+            for (int a = 0; a < 3; ++a) {
+                volatile float d = coords[3 * (p0 + i) + a] - mn[a];
+                volatile float s = d * inv;
+                float f = floorf(s);
+                int32_t q = f >= (float)ORC_VOXEL_MAX ? ORC_VOXEL_MAX : (int32_t)f;
+                if (q < 0) q = 0;
+                v[3 * i + a] = q;
+                if (q > vmax[a]) vmax[a] = q;
+            }
+
+        orc_hash_cfg cfg;
+        hash_cfg_fill(&cfg, hash, K, vmax, div_override, step_override);
+
+        /* capacities: every bucket holds bucket_size points, the last one what is left */
+        int64_t *cnt = (int64_t *)calloc((size_t)K, sizeof(int64_t));
+        int64_t *cap = (int64_t *)malloc(sizeof(int64_t) * (size_t)K);
+        for (int64_t j = 0; j < K; ++j) cap[j] = bucket_size;
+        cap[K - 1] = nb - (K - 1) * (int64_t)bucket_size;
+        int8_t *placed = (int8_t *)calloc((size_t)nb, 1);
+
+        /* step 0: direct hash (Algorithm 1, lines 5-9) */
+        for (int64_t i = 0; i < nb; ++i) {
+            int64_t j = hash_bucket(&cfg, &v[3 * i]);
+            if (cnt[j] < cap[j]) {
+                id[p0 + i] = (int32_t)j;
+                off[p0 + i] = (int32_t)cnt[j]++;
+                placed[i] = 1;
+                if (round_of) round_of[p0 + i] = 0;
+            }
+        }
+        /* steps 1..n_probes: Algorithm 2, one probe offset per step */
+        for (int32_t r = 1; r <= n_probes; ++r) {
+            for (int64_t i = 0; i < nb; ++i) {
+                if (placed[i]) continue;
+                int32_t w[3];
+                for (int a = 0; a < 3; ++a) {
+                    int64_t t = (int64_t)v[3 * i + a] + (int64_t)ORC_PROBE_DIR[r - 1][a] * cfg.step;
+                    if (t < 0) t = 0;
+                    if (t > vmax[a]) t = vmax[a];
+                    w[a] = (int32_t)t;
+                }
+                int64_t j = hash_bucket(&cfg, w);
+                if (cnt[j] < cap[j]) {
+                    id[p0 + i] = (int32_t)j;
+                    off[p0 + i] = (int32_t)cnt[j]++;
+                    placed[i] = 1;
+                    if (round_of) round_of[p0 + i] = r;
+                }
+            }
+        }
+        /* recycle (Algorithm 2, lines 19-22): leftovers fill the free slots, first bucket first */
+        int64_t j = 0;
+        for (int64_t i = 0; i < nb; ++i) {
+            if (placed[i]) continue;
+            while (cnt[j] >= cap[j]) ++j;
+            id[p0 + i] = (int32_t)j;
+            off[p0 + i] = (int32_t)cnt[j]++;
+            placed[i] = 1;
+            if (round_of) round_of[p0 + i] = n_probes + 1;
+        }
+
+        /* exclusive scan of the counters gives bucket_base (Algorithm 1, line 12) */
+        int64_t run = p0;
+        for (int64_t jj = 0; jj < K; ++jj) {
+            if (offsets) offsets[kbase + jj] = (int32_t)run;
+            run += cnt[jj];
+        }
+        if (offsets) offsets[kbase + K] = (int32_t)run;
+        /* scatter (Algorithm 1, line 13) */
+        int64_t *base = (int64_t *)malloc(sizeof(int64_t) * (size_t)K);
+        run = p0;
+        for (int64_t jj = 0; jj < K; ++jj) { base[jj] = run; run += cnt[jj]; }
+        for (int64_t i = p0; i < p1; ++i) {
+            int64_t row = base[id[i]] + off[i];
+            perm[row] = (int32_t)i;
+            if (inv_perm) inv_perm[i] = (int32_t)row;
+            if (bucket_id) bucket_id[i] = (int32_t)(kbase + id[i]);
+            if (bucket_off) bucket_off[i] = off[i];
+        }
+        free(base); free(placed); free(cap); free(cnt); free(v);
+        kbase += K;
+    }
+    if (scan_bucket_start) scan_bucket_start[n_scans] = (int32_t)kbase;
+    if (offsets && n_scans == 0) offsets[0] = 0;
+    free(id); free(off);
+    return kbase;
+}
+
+/* ------------------------------------------------------------------ regrouping (Section 4.2) */
+
+/* Scope (attention group) of the j-th bucket of a scan; m buckets per scope.
+ * plain:  consecutive windows of m buckets.
+ * shift:  the windows moved forward by s buckets; the first s buckets form a scope of their own.
+ * stride: every t-th bucket inside a block of m*t consecutive buckets. */
+int64_t orc_group_of_bucket(int64_t j, int32_t m, int32_t mode, int32_t s, int32_t t)
+{
+    if (mode == ORC_SHIFT) return (j + m - s) / m;
+    if (mode == ORC_STRIDE) return (j / ((int64_t)m * t)) * t + j % t;
+    return j / m;
+}
+
+/* ------------------------------------------------------------------ attention (Section 4.2) */
+
+static double bf16_to_double(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, sizeof(f));
+    return (double)f;
+}
+
+/*
+ * Multi-head self-attention restricted to scopes. q,k,v are bf16 bit patterns [n, heads*head_dim].
+ * Row p of the bucket-major array holds input row perm[p] (perm == NULL: inputs are already
+ * bucket-major). out[p, :] (binary64, bucket-major rows) = sum_j softmax_j(q_p . k_j * scale) v_j
+ * over the rows j of p's scope, head by head. row_sel (may be NULL) limits the computed query rows
+ * to those with row_sel[p] != 0; other rows of out are left untouched.
+ * returns the number of scopes visited, -1 on bad arguments.
+ */
+int64_t orc_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, const int32_t *perm,
+                 const int32_t *offsets, const int32_t *scan_bucket_start, int32_t n_scans,
+                 int32_t m, int32_t mode, int32_t s, int32_t t, int32_t heads, int32_t head_dim,
+                 double scale, const uint8_t *row_sel, double *out)
+{
+    if (m <= 0 || heads <= 0 || head_dim <= 0 || mode < 0 || mode > 2) return -1;
+    if (mode == ORC_SHIFT && (s <= 0 || s >= m)) return -1;
+    if (mode == ORC_STRIDE && t <= 0) return -1;
+    const int64_t C = (int64_t)heads * head_dim;
+    int64_t visited = 0;
+
+    for (int32_t b = 0; b < n_scans; ++b) {
+        const int64_t kb0 = scan_bucket_start[b], K = scan_bucket_start[b + 1] - kb0;
+        if (K <= 0) continue;
+        int64_t ngroups = 0;
+        for (int64_t j = 0; j < K; ++j) {
+            int64_t g = orc_group_of_bucket(j, m, mode, s, t);
+            if (g + 1 > ngroups) ngroups = g + 1;
+        }
+#pragma omp parallel for schedule(dynamic, 1) reduction(+ : visited)
+        for (int64_t g = 0; g < ngroups; ++g) {
+            /* rows of the scope: its buckets in increasing order, each a contiguous row range */
+            int64_t ng = 0;
+            for (int64_t j = 0; j < K; ++j)
+                if (orc_group_of_bucket(j, m, mode, s, t) == g) ng += offsets[kb0 + j + 1] - offsets[kb0 + j];
+            if (ng == 0) continue;
+            int64_t *rows = (int64_t *)malloc(sizeof(int64_t) * (size_t)ng);
+            int64_t c = 0;
+            for (int64_t j = 0; j < K; ++j)
+                if (orc_group_of_bucket(j, m, mode, s, t) == g)
+                    for (int64_t p = offsets[kb0 + j]; p < offsets[kb0 + j + 1]; ++p) rows[c++] = p;
+            double *sc = (double *)malloc(sizeof(double) * (size_t)ng);
+            ++visited;
+            for (int64_t a = 0; a < ng; ++a) {
+                const int64_t pa = rows[a];
+                if (row_sel && !row_sel[pa]) continue;
+                const int64_t ia = perm ? perm[pa] : pa;
+                for (int32_t h = 0; h < heads; ++h) {
+                    const int64_t co = (int64_t)h * head_dim;
+                    double mx = -INFINITY;
+                    for (int64_t bb = 0; bb < ng; ++bb) {
+                        const int64_t ib = perm ? perm[rows[bb]] : rows[bb];
+                        double dot = 0.0;
+                        for (int32_t e = 0; e < head_dim; ++e)
+                            dot += bf16_to_double(q[ia * C + co + e]) * bf16_to_double(k[ib * C + co + e]);
+                        sc[bb] = dot * scale;
+                        if (sc[bb] > mx) mx = sc[bb];
+                    }
+                    double den = 0.0;
+                    for (int64_t bb = 0; bb < ng; ++bb) {
+                        sc[bb] = exp(sc[bb] - mx);
+                        den += sc[bb];
+                    }
+                    for (int64_t bb = 0; bb < ng; ++bb) sc[bb] /= den; /* softmax row */
+                    for (int32_t e = 0; e < head_dim; ++e) {
+                        double acc = 0.0;
+                        for (int64_t bb = 0; bb < ng; ++bb) {
+                            const int64_t ib = perm ? perm[rows[bb]] : rows[bb];
+                            acc += sc[bb] * bf16_to_double(v[ib * C + co + e]);
+                        }
+                        out[pa * C + co + e] = acc;
+                    }
+                }
+            }
+            free(sc);
+            free(rows);
+        }
+    }
+    return visited;
+}
+
+/* Restore input order: dst[perm[p], :] = src[p, :] (the inverse of the one up-front scatter). */
+int orc_unpermute(const uint8_t *src, const int32_t *perm, int64_t n, int64_t row_bytes, uint8_t *dst)
+{
+    if (n < 0 || row_bytes < 0) return -1;
+    for (int64_t p = 0; p < n; ++p) memcpy(dst + (int64_t)perm[p] * row_bytes, src + p * row_bytes, (size_t)row_bytes);
+    return 0;
+}
+
+int orc_max_threads(void)
+{
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
