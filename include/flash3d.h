@@ -1,0 +1,159 @@
+/*
+ * flash3d.h - C ABI of the MI355X (gfx950) implementation of Flash3D's hot path
+ * (arXiv 2412.16481): Perfect-Spatial-Hashing bucketing of 3D points (Section 4.1,
+ * Algorithms 1 and 2) followed by Bucket-and-Swin multi-head self-attention (Section 4.2,
+ * Appendix "Bucket-Swin") and the inverse of the one up-front scatter.
+ *
+ * Conventions for every call
+ *   - Pointers are DEVICE pointers unless the comment says "host". The caller owns every buffer;
+ *     the library keeps no state between calls and allocates nothing.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream).
+ *     No call synchronises with the host, copies to the host, or reads device memory on the host.
+ *   - Return value: F3D_OK (0) or a negative F3D_ERR_* code. Argument errors are detected on the
+ *     host before anything is launched. Errors that only the device can see (inconsistent
+ *     batch_offsets) are reported through scan_bucket_start[n_scans] = -1, see f3d_psh_bucketize.
+ *   - NaN / Inf coordinates give unspecified (but memory-safe) bucket assignments.
+ *
+ * Vocabulary (paper -> here)
+ *   bucket            a PSH hash bucket of capacity S = bucket_cap / scope_buckets rows
+ *   attention scope   a group of up to `scope_buckets` buckets (at most bucket_cap rows) inside which
+ *                     attention is computed; plain, shifted and strided scopes regroup the SAME
+ *                     bucket-major layout (Section 4.2: no feature shuffling between passes)
+ *   bucket-major row  row p of the array obtained by scattering point i to
+ *                     bucket_base[bucket_id[i]] + bucket_offset[i] (Section 4.1, "Input and Output")
+ */
+#ifndef FLASH3D_H
+#define FLASH3D_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define F3D_OK 0
+#define F3D_ERR_INVALID_ARG (-1)         /* NULL required pointer, negative size, bad enum, ...          */
+#define F3D_ERR_BAD_ALIGNMENT (-2)       /* a pointer or row size is not aligned as documented           */
+#define F3D_ERR_WORKSPACE_TOO_SMALL (-3) /* workspace_bytes < f3d_workspace_bytes(...)                  */
+#define F3D_ERR_UNSUPPORTED (-4)         /* valid request outside the implemented limits                 */
+#define F3D_ERR_HIP (-5)                 /* a HIP runtime call failed; see f3d_last_hip_error()          */
+
+/* Hash functions of Section 4.1 ("Hash functions"). */
+#define F3D_HASH_XOR_MOD 0
+#define F3D_HASH_XOR_DIV 1
+#define F3D_HASH_ZORDER_MOD 2
+#define F3D_HASH_ZORDER_DIV 3
+
+/* Scope patterns of Section 4.2 and Table 2: plain windows, windows shifted by `shift` buckets,
+ * and scopes that take every `stride`-th bucket. */
+#define F3D_PLAIN 0
+#define F3D_SHIFT 1
+#define F3D_STRIDE 2
+
+#define F3D_MAX_PROBES 6          /* probe offsets of Algorithm 2: the six axis neighbours           */
+#define F3D_MAX_SCAN_BUCKETS 8192 /* most hash buckets one scan may own                               */
+#define F3D_MAX_SCOPE_BUCKETS 16  /* most buckets per attention scope                                 */
+#define F3D_MAX_VOXEL ((1 << 21) - 1) /* voxel coordinates saturate here (63-bit Morton code)        */
+
+/* Parameters of the bucketing (plain data; set struct_size = sizeof(f3d_params)). */
+typedef struct f3d_params {
+    uint32_t struct_size;
+    float voxel_size;        /* > 0; voxel coordinate = floor((c - scan minimum) * (1/voxel_size)), binary32 */
+    int32_t bucket_cap;      /* capacity of one attention scope in rows; multiple of 16*scope_buckets        */
+    int32_t scope_buckets;   /* buckets per scope (1..16); bucket capacity S = bucket_cap / scope_buckets    */
+    int32_t hash;            /* F3D_HASH_*                                                                   */
+    int32_t n_probes;        /* 0..6 rebalancing probes (Algorithm 2); 0 sends overflow straight to recycle  */
+    int32_t div;             /* divisor of the *_DIV hashes; 0 = automatic (largest code / K + 1)            */
+    int32_t probe_step;      /* probe distance in voxels; 0 = automatic                                      */
+    int64_t max_scan_points; /* upper bound on the points of any one scan; 0 = n. Sizes the workspace and    */
+                             /* must satisfy ceil(max_scan_points / S) <= F3D_MAX_SCAN_BUCKETS               */
+} f3d_params;
+
+/* Fill *p with the defaults: scope_buckets 4, Z-order-div hash, 6 probes, automatic divisor and step. */
+void f3d_params_default(f3d_params *p, float voxel_size, int32_t bucket_cap);
+
+/* Upper bound on the total number of hash buckets: n / S + n_scans. `offsets` needs this many + 1 ints. */
+int64_t f3d_max_buckets(int64_t n, int32_t n_scans, const f3d_params *p);
+
+/* Bytes of scratch device memory f3d_psh_bucketize needs (written to *out_bytes, host). */
+int f3d_workspace_bytes(int64_t n, int32_t n_scans, const f3d_params *p, size_t *out_bytes);
+
+/*
+ * PSH bucketing with rebalancing (Algorithms 1 and 2; Appendix "PSH with Two-Stage Counters").
+ * The racing atomics of the paper are replaced by a deterministic schedule with the same
+ * admissible result: all points take the same step together (direct hash, then probe 1, ...), and
+ * the points contending for a bucket in one step are served in increasing input index.
+ *
+ *   coords            [n,3] binary32, 4-byte aligned, scans stored back to back
+ *   batch_offsets     [n_scans+1] int32, non-decreasing, first 0, last n; NULL = one scan of n points
+ *   n, n_scans        0 <= n < 2^31 - 2^20; n_scans >= 1
+ *   perm       (out)  [n] perm[p] = input index of the point stored at bucket-major row p
+ *   inv_perm   (out)  [n] inv_perm[i] = bucket_base[bucket_id[i]] + bucket_offset[i]; may be NULL
+ *   offsets    (out)  [f3d_max_buckets()+1] first row of every bucket; entries past the last bucket = n
+ *   scan_bucket_start (out) [n_scans+1] first bucket of every scan; last entry = total buckets,
+ *                     or -1 if batch_offsets was inconsistent or a scan exceeded max_scan_points
+ *                     (then perm/inv_perm/offsets are unspecified; no out-of-bounds access happens)
+ *   placed_per_round (out) [8] int32, may be NULL: points placed by the direct hash, by probes 1..6,
+ *                     and by the recycle step
+ *   workspace         >= f3d_workspace_bytes(), 256-byte aligned; contents are scratch
+ * Every bucket of a scan ends up holding exactly S rows except the scan's last one, so
+ * offsets[first bucket of scan + j] = scan start + j*S ("any bucket-size-aligned sub-array is a bucket").
+ */
+int f3d_psh_bucketize(const float *coords, const int32_t *batch_offsets, int64_t n, int32_t n_scans,
+                      const f3d_params *p, int32_t *perm, int32_t *inv_perm, int32_t *offsets,
+                      int32_t *scan_bucket_start, int32_t *placed_per_round, void *workspace,
+                      size_t workspace_bytes, void *stream);
+
+/* The short form: one scan, default parameters. */
+static inline int f3d_psh_bucketize_simple(const float *coords, int64_t n, float voxel_size, int32_t bucket_cap,
+                                           int32_t *perm, int32_t *offsets, int32_t *scan_bucket_start,
+                                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    f3d_params p;
+    f3d_params_default(&p, voxel_size, bucket_cap);
+    return f3d_psh_bucketize(coords, NULL, n, 1, &p, perm, NULL, offsets, scan_bucket_start, NULL, workspace,
+                             workspace_bytes, stream);
+}
+
+/*
+ * Bucket-and-Swin multi-head self-attention, forward (Section 4.2 "Zero-Overhead Bucket-Swin
+ * Attention"; Appendix "Bucket-Swin"): exact softmax attention inside every scope, computed
+ * FlashAttention-style; the scope pattern only redirects which rows a tile is fetched from.
+ *
+ *   q, k, v     bf16 [n, heads*head_dim], row stride heads*head_dim elements, 16-byte aligned
+ *   perm        NULL: rows of q,k,v are already bucket-major. Otherwise row p is read from perm[p]
+ *   offsets, scan_bucket_start   as written by f3d_psh_bucketize (any layout with buckets of at most
+ *               bucket_cap/scope_buckets rows works)
+ *   max_buckets any upper bound on scan_bucket_start[n_scans] known on the host, e.g. f3d_max_buckets();
+ *               it only sizes the launch
+ *   bucket_cap, scope_buckets    as in f3d_params; a scope never has more than bucket_cap rows
+ *   mode        F3D_PLAIN | F3D_SHIFT | F3D_STRIDE
+ *   shift       buckets the windows are moved by, 0 < shift < scope_buckets (F3D_SHIFT only)
+ *   stride      distance between the buckets of a strided scope, >= 1 (F3D_STRIDE only)
+ *   heads, head_dim   head_dim is 16 or 32
+ *   softmax_scale     0 = 1/sqrt(head_dim)
+ *   out  (out)  bf16 [n, heads*head_dim], BUCKET-MAJOR rows: row p holds the result for the point stored
+ *               at row p (Appendix: input and output of a point sit at the same row)
+ * Arithmetic: bf16 operands, fp32 accumulation and softmax, probabilities rounded to bf16 before P*V.
+ */
+int f3d_bucket_swin_attn(const void *q, const void *k, const void *v, const int32_t *perm, const int32_t *offsets,
+                         const int32_t *scan_bucket_start, int64_t n, int32_t n_scans, int64_t max_buckets,
+                         int32_t bucket_cap, int32_t scope_buckets, int32_t mode, int32_t shift, int32_t stride, int32_t heads,
+                         int32_t head_dim, float softmax_scale, void *out, void *stream);
+
+/*
+ * Inverse of the up-front scatter (Section 4, "up-front global shuffle"): dst[perm[p], :] = src[p, :].
+ *   src, dst  [n, row_bytes] bytes; row_bytes > 0 and a multiple of 4; src != dst; 4-byte aligned
+ *             (16-byte aligned rows take the wide path)
+ */
+int f3d_unpermute(const void *src, const int32_t *perm, int64_t n, int32_t row_bytes, void *dst, void *stream);
+
+const char *f3d_error_string(int code); /* host string, static storage */
+int f3d_last_hip_error(void);           /* hipError_t of the last failed HIP call in this thread, 0 if none */
+int f3d_version(void);                  /* 1000*major + minor */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLASH3D_H */

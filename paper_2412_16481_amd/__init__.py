@@ -1,0 +1,184 @@
+"""Thin Python binding of libflash3d.so (the C ABI declared in include/flash3d.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels. torch is used for
+device memory and the current stream. There is no fallback: if the shared library is missing the
+import of the native handle fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libflash3d.so")
+
+F3D_OK = 0
+ERR_INVALID_ARG, ERR_BAD_ALIGNMENT, ERR_WORKSPACE_TOO_SMALL, ERR_UNSUPPORTED, ERR_HIP = -1, -2, -3, -4, -5
+HASHES = {"xor_mod": 0, "xor_div": 1, "zorder_mod": 2, "zorder_div": 3}
+MODES = {"plain": 0, "shift": 1, "stride": 2}
+
+EXPORTS = ("f3d_params_default", "f3d_max_buckets", "f3d_workspace_bytes", "f3d_psh_bucketize",
+           "f3d_bucket_swin_attn", "f3d_unpermute", "f3d_error_string", "f3d_last_hip_error", "f3d_version")
+
+
+class f3d_params(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("voxel_size", ctypes.c_float), ("bucket_cap", ctypes.c_int32),
+                ("scope_buckets", ctypes.c_int32), ("hash", ctypes.c_int32), ("n_probes", ctypes.c_int32),
+                ("div", ctypes.c_int32), ("probe_step", ctypes.c_int32), ("max_scan_points", ctypes.c_int64)]
+
+
+class Flash3DError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {error_string(code)} (code {code})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded shared library. Raises if it has not been built (python -m paper_2412_16481_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2412_16481_amd.build` "
+                              "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+        L.f3d_params_default.argtypes = [ctypes.POINTER(f3d_params), f32, i32]
+        L.f3d_params_default.restype = None
+        L.f3d_max_buckets.argtypes = [i64, i32, ctypes.POINTER(f3d_params)]
+        L.f3d_max_buckets.restype = i64
+        L.f3d_workspace_bytes.argtypes = [i64, i32, ctypes.POINTER(f3d_params), ctypes.POINTER(ctypes.c_size_t)]
+        L.f3d_workspace_bytes.restype = ctypes.c_int
+        L.f3d_psh_bucketize.argtypes = [vp, vp, i64, i32, ctypes.POINTER(f3d_params), vp, vp, vp, vp, vp, vp,
+                                        ctypes.c_size_t, vp]
+        L.f3d_psh_bucketize.restype = ctypes.c_int
+        L.f3d_bucket_swin_attn.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, i32, i32, i32, i32, i32, i32, f32, vp, vp]
+        L.f3d_bucket_swin_attn.restype = ctypes.c_int
+        L.f3d_unpermute.argtypes = [vp, vp, i64, i32, vp, vp]
+        L.f3d_unpermute.restype = ctypes.c_int
+        L.f3d_error_string.argtypes = [ctypes.c_int]
+        L.f3d_error_string.restype = ctypes.c_char_p
+        L.f3d_last_hip_error.restype = ctypes.c_int
+        L.f3d_version.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def error_string(code: int) -> str:
+    return lib().f3d_error_string(code).decode()
+
+
+def version() -> int:
+    return int(lib().f3d_version())
+
+
+def make_params(voxel_size: float, bucket_cap: int, scope_buckets: int = 4, hash: str = "zorder_div",
+                n_probes: int = 6, div: int = 0, probe_step: int = 0, max_scan_points: int = 0) -> f3d_params:
+    p = f3d_params()
+    lib().f3d_params_default(ctypes.byref(p), voxel_size, bucket_cap)
+    p.scope_buckets = scope_buckets
+    p.hash = HASHES[hash] if isinstance(hash, str) else int(hash)
+    p.n_probes = n_probes
+    p.div = div
+    p.probe_step = probe_step
+    p.max_scan_points = max_scan_points
+    return p
+
+
+def max_buckets(n: int, n_scans: int, params: f3d_params) -> int:
+    r = int(lib().f3d_max_buckets(n, n_scans, ctypes.byref(params)))
+    if r < 0:
+        raise Flash3DError(ERR_INVALID_ARG, "f3d_max_buckets")
+    return r
+
+
+def workspace_bytes(n: int, n_scans: int, params: f3d_params) -> int:
+    out = ctypes.c_size_t(0)
+    rc = lib().f3d_workspace_bytes(n, n_scans, ctypes.byref(params), ctypes.byref(out))
+    if rc != F3D_OK:
+        raise Flash3DError(rc, "f3d_workspace_bytes")
+    return int(out.value)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+@dataclass
+class Buckets:
+    """Device tensors written by f3d_psh_bucketize plus the host-side layout parameters."""
+    perm: "object"
+    inv_perm: "object"
+    offsets: "object"
+    scan_bucket_start: "object"
+    placed_per_round: "object"
+    n: int
+    n_scans: int
+    bucket_cap: int
+    scope_buckets: int
+    max_buckets: int = 0
+
+
+def psh_bucketize(coords, batch_offsets, params: f3d_params, workspace=None, out: Optional[Buckets] = None) -> Buckets:
+    """f3d_psh_bucketize on torch CUDA tensors. coords: float32 [n,3]; batch_offsets: int32 [n_scans+1] or None."""
+    import torch
+    assert coords.is_cuda and coords.dtype == torch.float32 and coords.is_contiguous()
+    n = int(coords.shape[0])
+    n_scans = 1 if batch_offsets is None else int(batch_offsets.shape[0]) - 1
+    if batch_offsets is not None:
+        assert batch_offsets.is_cuda and batch_offsets.dtype == torch.int32 and batch_offsets.is_contiguous()
+    dev = coords.device
+    if out is None:
+        kmax = max_buckets(n, n_scans, params)
+        out = Buckets(torch.empty(n, dtype=torch.int32, device=dev), torch.empty(n, dtype=torch.int32, device=dev),
+                      torch.empty(kmax + 1, dtype=torch.int32, device=dev),
+                      torch.empty(n_scans + 1, dtype=torch.int32, device=dev),
+                      torch.empty(8, dtype=torch.int32, device=dev), n, n_scans, params.bucket_cap, params.scope_buckets, kmax)
+    if workspace is None:
+        workspace = torch.empty(workspace_bytes(n, n_scans, params), dtype=torch.uint8, device=dev)
+    rc = lib().f3d_psh_bucketize(_ptr(coords), _ptr(batch_offsets), n, n_scans, ctypes.byref(params), _ptr(out.perm),
+                                 _ptr(out.inv_perm), _ptr(out.offsets), _ptr(out.scan_bucket_start),
+                                 _ptr(out.placed_per_round), _ptr(workspace), workspace.numel(), _stream())
+    if rc != F3D_OK:
+        raise Flash3DError(rc, "f3d_psh_bucketize")
+    return out
+
+
+def bucket_swin_attn(q, k, v, buckets: Buckets, heads: int, head_dim: int, mode: str = "plain", shift: int = 2,
+                     stride: int = 2, use_perm: bool = True, softmax_scale: float = 0.0, out=None):
+    """f3d_bucket_swin_attn. q,k,v: bfloat16 [n, heads*head_dim]; rows in input order when use_perm, else
+    already bucket-major. Returns bfloat16 [n, heads*head_dim] in bucket-major row order."""
+    import torch
+    for t in (q, k, v):
+        assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.shape == (buckets.n, heads * head_dim)
+    if out is None:
+        out = torch.empty_like(q)
+    rc = lib().f3d_bucket_swin_attn(_ptr(q), _ptr(k), _ptr(v), _ptr(buckets.perm) if use_perm else None,
+                                    _ptr(buckets.offsets), _ptr(buckets.scan_bucket_start), buckets.n, buckets.n_scans,
+                                    buckets.max_buckets, buckets.bucket_cap, buckets.scope_buckets, MODES[mode] if isinstance(mode, str) else mode,
+                                    shift, stride, heads, head_dim, softmax_scale, _ptr(out), _stream())
+    if rc != F3D_OK:
+        raise Flash3DError(rc, "f3d_bucket_swin_attn")
+    return out
+
+
+def unpermute(src, perm, out=None):
+    """f3d_unpermute: out[perm[p]] = src[p] for a contiguous 2-D tensor."""
+    import torch
+    assert src.is_cuda and src.is_contiguous() and src.dim() == 2
+    if out is None:
+        out = torch.empty_like(src)
+    rc = lib().f3d_unpermute(_ptr(src), _ptr(perm), int(src.shape[0]), int(src.shape[1] * src.element_size()), _ptr(out),
+                             _stream())
+    if rc != F3D_OK:
+        raise Flash3DError(rc, "f3d_unpermute")
+    return out

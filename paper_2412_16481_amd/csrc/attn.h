@@ -1,0 +1,34 @@
+// Internal interface between the C ABI (flash3d_api.hip) and the attention kernel (attn.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace f3d {
+
+constexpr int ATTN_BM = 128;  // query rows per workgroup
+
+struct AttnArgs {
+    const uint16_t* q;
+    const uint16_t* k;
+    const uint16_t* v;
+    uint16_t* out;
+    const int32_t* perm;     // may be null
+    const int32_t* offsets;
+    const int32_t* sbs;      // scan_bucket_start
+    int n;
+    int n_scans;
+    int m;        // buckets per scope
+    int mode;     // 0 plain, 1 shift, 2 stride
+    int shift;
+    int stride;
+    int H;
+    int C;        // row pitch in elements = heads * head_dim
+    float c_log2; // softmax scale * log2(e)
+    int n_slots;  // scope slots over all scans (upper bound, surplus workgroups exit)
+    int qblocks;  // query blocks per scope = ceil(bucket_cap / ATTN_BM)
+    int extra;    // spare slots per scan: 2 (plain, shift) or stride + 1
+};
+
+hipError_t attn_launch(const AttnArgs& a, int head_dim, hipStream_t stream);
+
+}  // namespace f3d

@@ -1,0 +1,303 @@
+// Bucket-and-Swin attention forward for gfx950 (Section 4.2; Appendix "Bucket-Swin").
+//
+// One workgroup = 4 waves = 128 query rows of one (scope, head). Keys/values of the scope stream
+// through LDS in stages of 128 rows, double buffered. Which rows a stage holds is index arithmetic on
+// the bucket offsets (plain / shifted / strided scope), so regrouping costs no pass over memory.
+//
+// Per 32-key tile a wave computes the TRANSPOSED score tile S^T = K Q^T with one 32x32x16 bf16 MFMA
+// per 16 head dims. In the MFMA result layout a lane then owns 16 keys of ONE query, so the running
+// max and the exponentials are per-lane work, and the fp32 result registers, rounded to bf16, already
+// are the B operand of the second MFMA O^T += V^T P^T as long as V^T is read from LDS in the matching
+// key order. No cross-lane shuffle of P, no LDS round trip.
+// For head_dim 16 the second MFMA has 16 spare output rows; row 16 multiplies P by ones, which yields
+// the softmax denominator on the matrix core instead of the vector ALU.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "attn.h"
+
+namespace f3d {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+
+constexpr int BM = ATTN_BM;     // query rows per workgroup
+constexpr int KT = 128;         // key rows per LDS stage
+constexpr int VSTR = KT + 8;    // row pitch of V^T in LDS (elements); keeps 16-byte alignment, staggers banks
+constexpr int MAXSEG = 16;
+
+union U4 {
+    uint4 u;
+    bf16x8 b;
+    uint16_t h[8];
+};
+
+__device__ __forceinline__ int find_slot_scan(const int* sbs, int n_scans, int m, int extra, int slot)
+{
+    // scans own disjoint slot ranges starting at sbs[b]/m + extra*b
+    int lo = 0, hi = n_scans;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (sbs[mid] / m + extra * mid <= slot) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    f32x2 x = {lo, hi};
+    bf16x2 y = __builtin_convertvector(x, bf16x2);  // v_cvt_pk_bf16_f32, round to nearest even
+    return *reinterpret_cast<uint32_t*>(&y);
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void k_attn(AttnArgs a)
+{
+    constexpr int NC = D / 8;              // 16-byte chunks of one head in a row
+    constexpr int KS = D / 16;             // MFMA k-steps for Q K^T
+    constexpr int LPT = KT * NC / 256;     // 16-byte loads per thread per stage and tensor
+    constexpr int SWZ_SHIFT = (NC == 2) ? 3 : 2;
+
+    __shared__ __attribute__((aligned(16))) uint16_t sK[2][KT * D];
+    __shared__ __attribute__((aligned(16))) uint16_t sV[2][D * VSTR];
+    __shared__ int seg_row0[MAXSEG];
+    __shared__ int seg_pre[MAXSEG + 1];
+    __shared__ int s_nseg;
+
+    // ---- which (scope, head, query block) is this workgroup: consecutive ids stay on one XCD
+    const int total = gridDim.x;  // multiple of 8
+    const int w = blockIdx.x;
+    const int u = (w & 7) * (total >> 3) + (w >> 3);
+    const int qb = u % a.qblocks;
+    const int head = (u / a.qblocks) % a.H;
+    const int slot = u / (a.qblocks * a.H);
+    if (slot >= a.n_slots) return;
+    if (a.sbs[a.n_scans] <= 0) return;
+    const int b = find_slot_scan(a.sbs, a.n_scans, a.m, a.extra, slot);
+    const int g = slot - (a.sbs[b] / a.m + a.extra * b);
+    const int kb0 = a.sbs[b], K = a.sbs[b + 1] - kb0;
+    if (K <= 0) return;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hf = lane >> 5;
+
+    // ---- rows of the scope: up to m segments (one bucket each; plain/shifted scopes are one run)
+    if (tid == 0) {
+        int nseg = 0, pre = 0;
+        const int m = a.m;
+        if (a.mode == 2) {
+            const int t = a.stride;
+            const int full = K / (m * t), rem = K - full * m * t;
+            const int ng = full * t + min(rem, t);
+            if (g < ng) {
+                const int j0 = (g / t) * m * t + (g % t);
+                for (int i = 0; i < m; ++i) {
+                    const int j = j0 + i * t;
+                    if (j >= K) break;
+                    const int r0 = a.offsets[kb0 + j], len = a.offsets[kb0 + j + 1] - r0;
+                    if (len <= 0) continue;
+                    seg_row0[nseg] = r0;
+                    seg_pre[nseg] = pre;
+                    pre += len;
+                    ++nseg;
+                }
+            }
+        } else {
+            int j0, j1;
+            if (a.mode == 1) {
+                j0 = g == 0 ? 0 : a.shift + (g - 1) * m;
+                j1 = g == 0 ? a.shift : j0 + m;
+            } else {
+                j0 = g * m;
+                j1 = j0 + m;
+            }
+            j1 = min(j1, K);
+            if (j0 < K) {
+                const int r0 = a.offsets[kb0 + j0], len = a.offsets[kb0 + j1] - r0;
+                if (len > 0) {
+                    seg_row0[0] = r0;
+                    seg_pre[0] = 0;
+                    pre = len;
+                    nseg = 1;
+                }
+            }
+        }
+        seg_pre[nseg] = pre;
+        s_nseg = nseg;
+    }
+    __syncthreads();
+    const int nseg = s_nseg;
+    if (nseg == 0) return;
+    const int ng = seg_pre[nseg];         // rows in this scope
+    if (qb * BM >= ng) return;
+
+    auto row_of = [&](int x) -> int {
+        int s = 0;
+        while (s + 1 < nseg && x >= seg_pre[s + 1]) ++s;
+        int r = seg_row0[s] + (x - seg_pre[s]);
+        return a.perm ? a.perm[r] : r;
+    };
+
+    const size_t hoff = (size_t)head * D;
+
+    // ---- this lane's query fragment: row l32 of the wave's 32 queries, dims 8*hf + 16*ks ..
+    const int xq = qb * BM + wave * 32 + l32;
+    U4 qf[KS];
+    {
+        const bool ok = xq < ng;
+        const size_t gr = ok ? (size_t)row_of(xq) : 0;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            qf[ks].u = make_uint4(0, 0, 0, 0);
+            if (ok) qf[ks].u = *reinterpret_cast<const uint4*>(a.q + gr * a.C + hoff + ks * 16 + hf * 8);
+        }
+    }
+
+    // ---- staging of K and V rows
+    U4 kreg[LPT], vreg[LPT];
+    auto load_stage = [&](int st) {
+#pragma unroll
+        for (int i = 0; i < LPT; ++i) {
+            const int uidx = tid + i * 256;
+            const int kk = uidx / NC, c = uidx % NC;
+            const int x = st * KT + kk;
+            kreg[i].u = make_uint4(0, 0, 0, 0);
+            vreg[i].u = make_uint4(0, 0, 0, 0);
+            if (x < ng) {
+                const size_t at = (size_t)row_of(x) * a.C + hoff + c * 8;
+                kreg[i].u = *reinterpret_cast<const uint4*>(a.k + at);
+                vreg[i].u = *reinterpret_cast<const uint4*>(a.v + at);
+            }
+        }
+    };
+    auto store_stage = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < LPT; ++i) {
+            const int uidx = tid + i * 256;
+            const int kk = uidx / NC, c = uidx % NC;
+            const int cs = c ^ ((kk >> SWZ_SHIFT) & (NC - 1));
+            *reinterpret_cast<uint4*>(&sK[buf][kk * D + cs * 8]) = kreg[i].u;
+            // V is stored transposed, keys of a 16-block reordered to the order the MFMA result holds them
+            const int w16 = kk & 15;
+            const int pos = (kk & ~15) + 8 * ((w16 >> 2) & 1) + 4 * (w16 >> 3) + (w16 & 3);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sV[buf][(c * 8 + e) * VSTR + pos] = vreg[i].h[e];
+        }
+    };
+
+    f32x16 o = {0};
+    float m_run = -INFINITY, l_run = 0.f;
+    const float cl2 = a.c_log2;
+    const int nst = (ng + KT - 1) / KT;
+
+    load_stage(0);
+    store_stage(0);
+    __syncthreads();
+
+    for (int st = 0; st < nst; ++st) {
+        const int buf = st & 1;
+        if (st + 1 < nst) load_stage(st + 1);
+
+#pragma unroll 1
+        for (int t4 = 0; t4 < KT / 32; ++t4) {
+            const int kbase = st * KT + t4 * 32;
+            if (kbase >= ng) break;
+            // S^T tile: rows = 32 keys, cols = 32 queries
+            f32x16 s = {0};
+            const int kk = t4 * 32 + l32;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const int c = 2 * ks + hf;
+                const int cs = c ^ ((kk >> SWZ_SHIFT) & (NC - 1));
+                U4 kf;
+                kf.u = *reinterpret_cast<const uint4*>(&sK[buf][kk * D + cs * 8]);
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.b, qf[ks].b, s, 0, 0, 0);
+            }
+            if (kbase + 32 > ng) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = kbase + 8 * (r >> 2) + 4 * hf + (r & 3);
+                    if (key >= ng) s[r] = -INFINITY;
+                }
+            }
+            float mx = s[0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m_run, mx * cl2);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            m_run = m_new;
+            float p[16];
+            float psum = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                p[r] = __builtin_amdgcn_exp2f(s[r] * cl2 - m_new);
+                if (D == 32) psum += p[r];
+            }
+            if (D == 32) l_run = l_run * alpha + psum;
+            constexpr int NO = (D == 16) ? 9 : 16;
+#pragma unroll
+            for (int r = 0; r < NO; ++r) o[r] *= alpha;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                union { uint32_t u[4]; bf16x8 b; } pb;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pb.u[e] = pack_bf16(p[8 * t + 2 * e], p[8 * t + 2 * e + 1]);
+                U4 vf;
+                const int dim = (D == 16) ? (l32 & 15) : l32;
+                vf.u = *reinterpret_cast<const uint4*>(&sV[buf][dim * VSTR + t4 * 32 + 16 * t + 8 * hf]);
+                if (D == 16) {
+                    if (l32 == 16) vf.u = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
+                    if (l32 > 16) vf.u = make_uint4(0, 0, 0, 0);
+                }
+                o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.b, pb.b, o, 0, 0, 0);
+            }
+        }
+
+        if (st + 1 < nst) store_stage(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: divide by the softmax denominator, round to bf16, store at the query's own row
+    float den;
+    if (D == 16) {
+        den = __shfl(o[8], l32, 64);       // row 16 of O^T lives in the lower half-wave
+    } else {
+        den = l_run + __shfl_xor(l_run, 32, 64);
+    }
+    if (xq < ng) {
+        const float inv = 1.0f / den;
+        int s = 0;
+        while (s + 1 < nseg && xq >= seg_pre[s + 1]) ++s;
+        const size_t orow = (size_t)(seg_row0[s] + (xq - seg_pre[s]));   // bucket-major row, never through perm
+        uint16_t* dst = a.out + orow * a.C + hoff;
+        constexpr int NB = D / 8;
+#pragma unroll
+        for (int blk = 0; blk < NB; ++blk) {
+            uint2 pk;
+            pk.x = pack_bf16(o[4 * blk] * inv, o[4 * blk + 1] * inv);
+            pk.y = pack_bf16(o[4 * blk + 2] * inv, o[4 * blk + 3] * inv);
+            *reinterpret_cast<uint2*>(dst + 8 * blk + 4 * hf) = pk;
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t attn_launch(const AttnArgs& a, int head_dim, hipStream_t stream)
+{
+    long long total = (long long)a.n_slots * a.H * a.qblocks;
+    total = (total + 7) / 8 * 8;
+    if (total == 0) return hipSuccess;
+    if (head_dim == 16)
+        k_attn<16><<<(unsigned)total, 256, 0, stream>>>(a);
+    else
+        k_attn<32><<<(unsigned)total, 256, 0, stream>>>(a);
+    return hipGetLastError();
+}
+
+}  // namespace f3d

@@ -1,0 +1,274 @@
+// C ABI of the library: argument checks on the host, workspace carving, kernel launches.
+// Declarations and the meaning of every argument are in include/flash3d.h.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+#include "attn.h"
+#include "flash3d.h"
+#include "psh.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e)
+{
+    g_last_hip_error = (int)e;
+    return F3D_ERR_HIP;
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Plan {
+    int S;
+    int kcap;
+    long long max_scan_points;
+    long long max_buckets;
+    long long chunks;
+    size_t bytes;
+    // offsets (bytes) of the workspace arrays
+    size_t o_status, o_p0, o_c0, o_mm, o_cnt, o_cnt2, o_hist, o_key, o_left, o_leftpre, o_freepre, o_inv, o_rc;
+};
+
+int check_params(int64_t n, int32_t n_scans, const f3d_params* p)
+{
+    if (!p || p->struct_size != sizeof(f3d_params)) return F3D_ERR_INVALID_ARG;
+    if (n < 0 || n_scans < 1) return F3D_ERR_INVALID_ARG;
+    if (!(p->voxel_size > 0.0f) || !isfinite(p->voxel_size)) return F3D_ERR_INVALID_ARG;
+    if (p->scope_buckets < 1 || p->bucket_cap < 1) return F3D_ERR_INVALID_ARG;
+    if (p->hash < 0 || p->hash > 3) return F3D_ERR_INVALID_ARG;
+    if (p->n_probes < 0 || p->n_probes > F3D_MAX_PROBES) return F3D_ERR_INVALID_ARG;
+    if (p->div < 0 || p->probe_step < 0 || p->max_scan_points < 0) return F3D_ERR_INVALID_ARG;
+    if (p->bucket_cap % (16 * p->scope_buckets) != 0) return F3D_ERR_INVALID_ARG;
+    if (p->scope_buckets > F3D_MAX_SCOPE_BUCKETS) return F3D_ERR_UNSUPPORTED;
+    if (n >= (int64_t)2147483647 - (1 << 20)) return F3D_ERR_UNSUPPORTED;
+    if (n_scans > 65535) return F3D_ERR_UNSUPPORTED;
+    const long long S = p->bucket_cap / p->scope_buckets;
+    long long msp = p->max_scan_points > 0 ? p->max_scan_points : n;
+    if (msp > n) msp = n;
+    if ((msp + S - 1) / S > F3D_MAX_SCAN_BUCKETS) return F3D_ERR_UNSUPPORTED;
+    return F3D_OK;
+}
+
+void make_plan(int64_t n, int32_t n_scans, const f3d_params* p, Plan* pl)
+{
+    pl->S = p->bucket_cap / p->scope_buckets;
+    long long msp = p->max_scan_points > 0 ? p->max_scan_points : n;
+    if (msp > n) msp = n;
+    pl->max_scan_points = msp;
+    long long kcap = (msp + pl->S - 1) / pl->S;
+    if (kcap < 1) kcap = 1;
+    pl->kcap = (int)kcap;
+    pl->max_buckets = n / pl->S + n_scans;
+    pl->chunks = n / f3d::PSH_CHUNK + n_scans;
+    size_t at = 0;
+    auto take = [&](size_t bytes) { size_t o = at; at = align_up(at + bytes, 256); return o; };
+    pl->o_status = take(16);
+    pl->o_rc = take(8 * 4);
+    pl->o_p0 = take((size_t)(n_scans + 1) * 4);
+    pl->o_c0 = take((size_t)(n_scans + 1) * 4);
+    pl->o_mm = take((size_t)n_scans * 8 * 4);
+    pl->o_cnt = take((size_t)(pl->max_buckets + 1) * 4);
+    pl->o_cnt2 = take((size_t)(pl->max_buckets + 1) * 4);
+    pl->o_freepre = take((size_t)(pl->max_buckets + 1) * 4);
+    pl->o_left = take((size_t)pl->chunks * 4);
+    pl->o_leftpre = take((size_t)pl->chunks * 4);
+    pl->o_hist = take((size_t)pl->chunks * pl->kcap * 4);
+    pl->o_key = take((size_t)n * 4);
+    pl->o_inv = take((size_t)n * 4);
+    pl->bytes = at;
+}
+
+__global__ void k_unpermute16(const uint4* __restrict__ src, const int32_t* __restrict__ perm, long long n, int vec_per_row,
+                              uint4* __restrict__ dst)
+{
+    const long long total = n * vec_per_row;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+        const long long p = i / vec_per_row;
+        const int c = (int)(i - p * vec_per_row);
+        dst[(long long)perm[p] * vec_per_row + c] = src[i];
+    }
+}
+
+__global__ void k_unpermute4(const uint32_t* __restrict__ src, const int32_t* __restrict__ perm, long long n, int w_per_row,
+                             uint32_t* __restrict__ dst)
+{
+    const long long total = n * w_per_row;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+        const long long p = i / w_per_row;
+        const int c = (int)(i - p * w_per_row);
+        dst[(long long)perm[p] * w_per_row + c] = src[i];
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+void f3d_params_default(f3d_params* p, float voxel_size, int32_t bucket_cap)
+{
+    if (!p) return;
+    memset(p, 0, sizeof(*p));
+    p->struct_size = sizeof(f3d_params);
+    p->voxel_size = voxel_size;
+    p->bucket_cap = bucket_cap;
+    p->scope_buckets = 4;
+    p->hash = F3D_HASH_ZORDER_DIV;
+    p->n_probes = F3D_MAX_PROBES;
+}
+
+int64_t f3d_max_buckets(int64_t n, int32_t n_scans, const f3d_params* p)
+{
+    if (check_params(n, n_scans, p) != F3D_OK) return -1;
+    return n / (p->bucket_cap / p->scope_buckets) + n_scans;
+}
+
+int f3d_workspace_bytes(int64_t n, int32_t n_scans, const f3d_params* p, size_t* out_bytes)
+{
+    if (!out_bytes) return F3D_ERR_INVALID_ARG;
+    const int rc = check_params(n, n_scans, p);
+    if (rc != F3D_OK) return rc;
+    Plan pl;
+    make_plan(n, n_scans, p, &pl);
+    *out_bytes = pl.bytes;
+    return F3D_OK;
+}
+
+int f3d_psh_bucketize(const float* coords, const int32_t* batch_offsets, int64_t n, int32_t n_scans, const f3d_params* p,
+                      int32_t* perm, int32_t* inv_perm, int32_t* offsets, int32_t* scan_bucket_start,
+                      int32_t* placed_per_round, void* workspace, size_t workspace_bytes, void* stream)
+{
+    const int rc = check_params(n, n_scans, p);
+    if (rc != F3D_OK) return rc;
+    if (!offsets || !scan_bucket_start || !workspace) return F3D_ERR_INVALID_ARG;
+    if (n > 0 && (!coords || !perm)) return F3D_ERR_INVALID_ARG;
+    if (((uintptr_t)coords | (uintptr_t)batch_offsets | (uintptr_t)perm | (uintptr_t)inv_perm | (uintptr_t)offsets |
+         (uintptr_t)scan_bucket_start | (uintptr_t)placed_per_round) & 3)
+        return F3D_ERR_BAD_ALIGNMENT;
+    if ((uintptr_t)workspace & 255) return F3D_ERR_BAD_ALIGNMENT;
+    Plan pl;
+    make_plan(n, n_scans, p, &pl);
+    if (workspace_bytes < pl.bytes) return F3D_ERR_WORKSPACE_TOO_SMALL;
+
+    char* ws = (char*)workspace;
+    f3d::PshArgs a;
+    memset(&a, 0, sizeof(a));
+    a.coords = coords;
+    a.batch_offsets = batch_offsets;
+    a.n = (int)n;
+    a.n_scans = n_scans;
+    a.inv_voxel = 1.0f / p->voxel_size;
+    a.S = pl.S;
+    a.hash = p->hash;
+    a.n_probes = p->n_probes;
+    a.div = p->div;
+    a.step = p->probe_step;
+    a.kcap = pl.kcap;
+    a.max_scan_points = pl.max_scan_points;
+    a.max_buckets = (int)pl.max_buckets;
+    a.perm = perm;
+    a.inv_perm = inv_perm ? inv_perm : (int32_t*)(ws + pl.o_inv);
+    a.offsets = offsets;
+    a.sbs = scan_bucket_start;
+    a.round_count = placed_per_round ? placed_per_round : (int32_t*)(ws + pl.o_rc);
+    a.status = (int32_t*)(ws + pl.o_status);
+    a.scan_p0 = (int32_t*)(ws + pl.o_p0);
+    a.scan_c0 = (int32_t*)(ws + pl.o_c0);
+    a.mm = (uint32_t*)(ws + pl.o_mm);
+    a.cnt = (int32_t*)(ws + pl.o_cnt);
+    a.cnt_next = (int32_t*)(ws + pl.o_cnt2);
+    a.hist = (int32_t*)(ws + pl.o_hist);
+    a.key = (uint32_t*)(ws + pl.o_key);
+    a.left = (int32_t*)(ws + pl.o_left);
+    a.leftpre = (int32_t*)(ws + pl.o_leftpre);
+    a.freepre = (int32_t*)(ws + pl.o_freepre);
+    const hipError_t e = f3d::psh_launch(a, (hipStream_t)stream);
+    return e == hipSuccess ? F3D_OK : hip_fail(e);
+}
+
+int f3d_bucket_swin_attn(const void* q, const void* k, const void* v, const int32_t* perm, const int32_t* offsets,
+                         const int32_t* scan_bucket_start, int64_t n, int32_t n_scans, int64_t max_buckets,
+                         int32_t bucket_cap, int32_t scope_buckets, int32_t mode, int32_t shift, int32_t stride, int32_t heads,
+                         int32_t head_dim, float softmax_scale, void* out, void* stream)
+{
+    if (n < 0 || n_scans < 1 || heads < 1 || bucket_cap < 1 || scope_buckets < 1 || max_buckets < 0) return F3D_ERR_INVALID_ARG;
+    if (mode < F3D_PLAIN || mode > F3D_STRIDE) return F3D_ERR_INVALID_ARG;
+    if (bucket_cap % (16 * scope_buckets) != 0) return F3D_ERR_INVALID_ARG;
+    if (mode == F3D_SHIFT && (shift <= 0 || shift >= scope_buckets)) return F3D_ERR_INVALID_ARG;
+    if (mode == F3D_STRIDE && stride < 1) return F3D_ERR_INVALID_ARG;
+    if (!(softmax_scale >= 0.0f) || !isfinite(softmax_scale)) return F3D_ERR_INVALID_ARG;
+    if (head_dim != 16 && head_dim != 32) return F3D_ERR_UNSUPPORTED;
+    if (scope_buckets > F3D_MAX_SCOPE_BUCKETS || stride > 4096 || n_scans > 65535) return F3D_ERR_UNSUPPORTED;
+    if (n >= (int64_t)2147483647 - (1 << 20) || (long long)heads * head_dim > 65536) return F3D_ERR_UNSUPPORTED;
+    if (!offsets || !scan_bucket_start) return F3D_ERR_INVALID_ARG;
+    if (n == 0) return F3D_OK;
+    if (!q || !k || !v || !out) return F3D_ERR_INVALID_ARG;
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) return F3D_ERR_BAD_ALIGNMENT;
+    if (((uintptr_t)perm | (uintptr_t)offsets | (uintptr_t)scan_bucket_start) & 3) return F3D_ERR_BAD_ALIGNMENT;
+
+    f3d::AttnArgs a;
+    memset(&a, 0, sizeof(a));
+    a.q = (const uint16_t*)q;
+    a.k = (const uint16_t*)k;
+    a.v = (const uint16_t*)v;
+    a.out = (uint16_t*)out;
+    a.perm = perm;
+    a.offsets = offsets;
+    a.sbs = scan_bucket_start;
+    a.n = (int)n;
+    a.n_scans = n_scans;
+    a.m = scope_buckets;
+    a.mode = mode;
+    a.shift = shift;
+    a.stride = stride;
+    a.H = heads;
+    a.C = heads * head_dim;
+    const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / sqrtf((float)head_dim);
+    a.c_log2 = scale * 1.44269504088896340736f;
+    a.extra = mode == F3D_STRIDE ? stride + 1 : 2;
+    const long long slots = max_buckets / scope_buckets + (long long)a.extra * n_scans + 1;
+    a.qblocks = (bucket_cap + f3d::ATTN_BM - 1) / f3d::ATTN_BM;
+    if (slots * heads * a.qblocks > 2000000000ll) return F3D_ERR_UNSUPPORTED;
+    a.n_slots = (int)slots;
+    const hipError_t e = f3d::attn_launch(a, head_dim, (hipStream_t)stream);
+    return e == hipSuccess ? F3D_OK : hip_fail(e);
+}
+
+int f3d_unpermute(const void* src, const int32_t* perm, int64_t n, int32_t row_bytes, void* dst, void* stream)
+{
+    if (n < 0 || row_bytes <= 0 || (row_bytes & 3)) return F3D_ERR_INVALID_ARG;
+    if (n == 0) return F3D_OK;
+    if (!src || !perm || !dst || src == dst) return F3D_ERR_INVALID_ARG;
+    if (((uintptr_t)src | (uintptr_t)dst | (uintptr_t)perm) & 3) return F3D_ERR_BAD_ALIGNMENT;
+    const bool wide = (row_bytes % 16 == 0) && ((((uintptr_t)src | (uintptr_t)dst) & 15) == 0);
+    const long long units = n * (wide ? row_bytes / 16 : row_bytes / 4);
+    long long blocks = (units + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    if (wide)
+        k_unpermute16<<<(unsigned)blocks, 256, 0, (hipStream_t)stream>>>((const uint4*)src, perm, n, row_bytes / 16, (uint4*)dst);
+    else
+        k_unpermute4<<<(unsigned)blocks, 256, 0, (hipStream_t)stream>>>((const uint32_t*)src, perm, n, row_bytes / 4, (uint32_t*)dst);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? F3D_OK : hip_fail(e);
+}
+
+const char* f3d_error_string(int code)
+{
+    switch (code) {
+        case F3D_OK: return "ok";
+        case F3D_ERR_INVALID_ARG: return "invalid argument";
+        case F3D_ERR_BAD_ALIGNMENT: return "pointer or row size not aligned as required";
+        case F3D_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case F3D_ERR_UNSUPPORTED: return "request outside the implemented limits";
+        case F3D_ERR_HIP: return "HIP runtime error";
+        default: return "unknown error code";
+    }
+}
+
+int f3d_last_hip_error(void) { return g_last_hip_error; }
+
+int f3d_version(void) { return 1; }
+
+}  // extern "C"

@@ -1,0 +1,50 @@
+// Internal interface between the C ABI (flash3d_api.hip) and the bucketing kernels (psh.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace f3d {
+
+constexpr int PSH_CHUNK = 1024;   // points one workgroup ranks
+constexpr int PSH_THREADS = 256;
+constexpr int PSH_WAVES = PSH_THREADS / 64;
+constexpr int F3D_VOXEL_MAX = (1 << 21) - 1;
+
+struct PshArgs {
+    // inputs
+    const float* coords;
+    const int32_t* batch_offsets;  // may be null: one scan
+    int n;
+    int n_scans;
+    float inv_voxel;
+    int S;       // bucket capacity
+    int hash;
+    int n_probes;
+    int div;
+    int step;
+    int kcap;    // pitch of the count matrix = most buckets a scan may have
+    long long max_scan_points;
+    int max_buckets;
+    // outputs
+    int32_t* perm;
+    int32_t* inv_perm;
+    int32_t* offsets;
+    int32_t* sbs;          // scan_bucket_start
+    int32_t* round_count;  // [8]
+    // workspace
+    int32_t* status;   // [4]
+    int32_t* scan_p0;  // [n_scans+1]
+    int32_t* scan_c0;  // [n_scans+1] first chunk of every scan
+    uint32_t* mm;      // [n_scans][8] bounding box as ordered ints
+    int32_t* cnt;      // [max_buckets] fill level of every bucket
+    int32_t* cnt_next;
+    int32_t* hist;     // [chunks][kcap]
+    uint32_t* key;     // [n] per point: (bucket << 12 | rank inside chunk) or KEY_PLACED
+    int32_t* left;     // [chunks] leftovers per chunk
+    int32_t* leftpre;  // [chunks]
+    int32_t* freepre;  // [max_buckets]
+};
+
+hipError_t psh_launch(const PshArgs& args, hipStream_t stream);
+
+}  // namespace f3d

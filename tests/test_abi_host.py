@@ -1,0 +1,137 @@
+"""Host-side checks of the C ABI (no GPU): the library loads, exports every declared symbol, and
+refuses bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2412_16481_amd as f3d
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "flash3d.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(f3d_[a-z0-9_]+)\s*\(", text))
+    names.discard("f3d_psh_bucketize_simple")          # static inline wrapper in the header
+    return sorted(names)
+
+
+def test_library_exports_every_declared_symbol():
+    L = f3d.lib()
+    names = declared_symbols()
+    assert set(names) == set(f3d.EXPORTS)
+    for name in names:
+        assert getattr(L, name) is not None
+    assert f3d.version() >= 1
+
+
+def test_params_default_and_sizes():
+    p = f3d.make_params(0.02, 1024)
+    assert p.struct_size == ctypes.sizeof(f3d.f3d_params)
+    assert (p.scope_buckets, p.hash, p.n_probes, p.div, p.probe_step) == (4, 3, 6, 0, 0)
+    assert f3d.max_buckets(200_000, 1, p) == 200_000 // 256 + 1
+    assert f3d.workspace_bytes(200_000, 1, p) > 200_000 * 8
+    assert f3d.workspace_bytes(0, 1, p) > 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(voxel_size=0.0), f3d.ERR_INVALID_ARG),
+    (dict(voxel_size=-1.0), f3d.ERR_INVALID_ARG),
+    (dict(voxel_size=float("nan")), f3d.ERR_INVALID_ARG),
+    (dict(bucket_cap=1000), f3d.ERR_INVALID_ARG),            # not a multiple of 16 * scope_buckets
+    (dict(scope_buckets=0), f3d.ERR_INVALID_ARG),
+    (dict(scope_buckets=32, bucket_cap=1024), f3d.ERR_UNSUPPORTED),
+    (dict(hash=7), f3d.ERR_INVALID_ARG),
+    (dict(n_probes=7), f3d.ERR_INVALID_ARG),
+    (dict(n_probes=-1), f3d.ERR_INVALID_ARG),
+    (dict(div=-1), f3d.ERR_INVALID_ARG),
+    (dict(n=-1), f3d.ERR_INVALID_ARG),
+    (dict(n_scans=0), f3d.ERR_INVALID_ARG),
+    (dict(n=10_000_000, bucket_cap=64), f3d.ERR_UNSUPPORTED),  # one scan would own > 8192 buckets
+    (dict(struct_size=4), f3d.ERR_INVALID_ARG),
+])
+def test_workspace_query_refuses_bad_parameters(kw, code):
+    kw = dict(kw)
+    n = kw.pop("n", 1000)
+    n_scans = kw.pop("n_scans", 1)
+    struct_size = kw.pop("struct_size", None)
+    base = dict(voxel_size=0.02, bucket_cap=1024)
+    base.update(kw)
+    p = f3d.make_params(**base)
+    if struct_size is not None:
+        p.struct_size = struct_size
+    out = ctypes.c_size_t(0)
+    assert f3d.lib().f3d_workspace_bytes(n, n_scans, ctypes.byref(p), ctypes.byref(out)) == code
+
+
+def test_max_scan_points_lifts_the_bucket_limit():
+    p = f3d.make_params(0.02, 64, max_scan_points=100_000)
+    assert f3d.workspace_bytes(10_000_000, 200, p) > 0
+
+
+def test_bucketize_refuses_null_and_misaligned_pointers_on_the_host():
+    L = f3d.lib()
+    p = f3d.make_params(0.02, 1024)
+    fake = 0x10000  # never dereferenced: the checks fail first
+    args = lambda **o: [o.get("coords", fake), None, 100, 1, ctypes.byref(p), o.get("perm", fake), None,
+                        o.get("offsets", fake), o.get("sbs", fake), None, o.get("ws", fake), o.get("wsb", 1 << 30), None]
+    assert L.f3d_psh_bucketize(*args(coords=None)) == f3d.ERR_INVALID_ARG
+    assert L.f3d_psh_bucketize(*args(perm=None)) == f3d.ERR_INVALID_ARG
+    assert L.f3d_psh_bucketize(*args(offsets=None)) == f3d.ERR_INVALID_ARG
+    assert L.f3d_psh_bucketize(*args(ws=None)) == f3d.ERR_INVALID_ARG
+    assert L.f3d_psh_bucketize(*args(coords=fake + 2)) == f3d.ERR_BAD_ALIGNMENT
+    assert L.f3d_psh_bucketize(*args(ws=fake + 64)) == f3d.ERR_BAD_ALIGNMENT
+    assert L.f3d_psh_bucketize(*args(wsb=16)) == f3d.ERR_WORKSPACE_TOO_SMALL
+
+
+def test_attention_refuses_bad_arguments_on_the_host():
+    L = f3d.lib()
+    fake = 0x10000
+    def call(**o):
+        return L.f3d_bucket_swin_attn(o.get("q", fake), fake, fake, None, o.get("offsets", fake), fake, o.get("n", 100), 1, 10,
+                                      o.get("cap", 1024), o.get("m", 4), o.get("mode", 0), o.get("shift", 2),
+                                      o.get("stride", 2), o.get("heads", 4), o.get("d", 16), o.get("scale", 0.0), fake, None)
+    assert call(d=24) == f3d.ERR_UNSUPPORTED
+    assert call(d=64) == f3d.ERR_UNSUPPORTED
+    assert call(mode=3) == f3d.ERR_INVALID_ARG
+    assert call(mode=1, shift=0) == f3d.ERR_INVALID_ARG
+    assert call(mode=1, shift=4) == f3d.ERR_INVALID_ARG
+    assert call(mode=2, stride=0) == f3d.ERR_INVALID_ARG
+    assert call(cap=1000) == f3d.ERR_INVALID_ARG
+    assert call(heads=0) == f3d.ERR_INVALID_ARG
+    assert call(scale=-1.0) == f3d.ERR_INVALID_ARG
+    assert call(q=None) == f3d.ERR_INVALID_ARG
+    assert call(q=fake + 2) == f3d.ERR_BAD_ALIGNMENT
+    assert call(offsets=None) == f3d.ERR_INVALID_ARG
+    assert call(n=-5) == f3d.ERR_INVALID_ARG
+    assert call(n=0) == f3d.F3D_OK                      # nothing to do, nothing launched
+
+
+def test_unpermute_refuses_bad_arguments_on_the_host():
+    L = f3d.lib()
+    fake = 0x10000
+    assert L.f3d_unpermute(fake, fake, 10, 0, fake + 4096, None) == f3d.ERR_INVALID_ARG
+    assert L.f3d_unpermute(fake, fake, 10, 6, fake + 4096, None) == f3d.ERR_INVALID_ARG
+    assert L.f3d_unpermute(fake, fake, 10, 128, fake, None) == f3d.ERR_INVALID_ARG      # in place
+    assert L.f3d_unpermute(None, fake, 10, 128, fake, None) == f3d.ERR_INVALID_ARG
+    assert L.f3d_unpermute(fake + 1, fake, 10, 128, fake + 4096, None) == f3d.ERR_BAD_ALIGNMENT
+    assert L.f3d_unpermute(fake, fake, 0, 128, fake + 4096, None) == f3d.F3D_OK
+
+
+def test_error_strings():
+    assert f3d.error_string(0) == "ok"
+    for c in (-1, -2, -3, -4, -5):
+        assert f3d.error_string(c) not in ("ok", "unknown error code")
+    assert f3d.error_string(-99) == "unknown error code"
+
+
+def test_product_package_never_touches_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2412_16481_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "orc_" not in text, fn

@@ -1,0 +1,294 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded inputs.
+
+Bucketing is integer work: perm, inv_perm, offsets, scan_bucket_start and the per-round placement
+counts must match bit for bit. Attention is compared element by element within max-abs 1e-2
+(bf16 inputs and outputs, fp32 accumulation on the GPU; binary64 in the oracle); at the full
+benchmark sizes the comparison runs on sampled query rows, each computed in full by the oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2412_16481_amd as f3d
+from paper_2412_16481_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+ATOL = 1e-2   # max-abs bound on attention outputs
+HASHES = ["xor_mod", "xor_div", "zorder_mod", "zorder_div"]
+DEV = "cuda:0"
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.view(dtype)
+    return t.to(DEV)
+
+
+def run_bucketize(coords, bo, voxel, cap, m=4, hash="zorder_div", n_probes=6, max_scan_points=0, div=0, probe_step=0):
+    p = f3d.make_params(voxel, cap, m, hash, n_probes, div, probe_step, max_scan_points)
+    bk = f3d.psh_bucketize(dev(coords), None if bo is None else dev(bo.astype(np.int32)), p)
+    torch.cuda.synchronize()
+    return bk
+
+
+def check_bucketize(coords, bo, voxel, cap, m=4, hash="zorder_div", n_probes=6, **kw):
+    S = cap // m
+    bo_arr = np.array([0, coords.shape[0]], dtype=np.int32) if bo is None else bo
+    ref = oracle.bucketize(coords, bo_arr, voxel, S, hash, n_probes, kw.get("div", 0), kw.get("probe_step", 0))
+    bk = run_bucketize(coords, bo, voxel, cap, m, hash, n_probes, **kw)
+    K = len(ref["offsets"]) - 1
+    assert bk.scan_bucket_start.cpu().numpy().tolist() == ref["scan_bucket_start"].tolist()
+    assert np.array_equal(bk.offsets.cpu().numpy()[:K + 1], ref["offsets"])
+    assert (bk.offsets.cpu().numpy()[K:] == coords.shape[0]).all()
+    assert np.array_equal(bk.perm.cpu().numpy(), ref["perm"])
+    assert np.array_equal(bk.inv_perm.cpu().numpy(), ref["inv_perm"])
+    rc = np.bincount(ref["round_of"], minlength=8)[:8] if coords.shape[0] else np.zeros(8, dtype=np.int64)
+    assert bk.placed_per_round.cpu().numpy().tolist() == rc.tolist()
+    return bk, ref
+
+
+# ----------------------------------------------------------------------------- bucketize
+
+
+@pytest.mark.parametrize("name", wl.CONFIG_NAMES)
+@pytest.mark.parametrize("hash", HASHES)
+def test_bucketize_matches_oracle_on_workloads(name, hash):
+    w = wl.make_workload(name)
+    check_bucketize(w.coords, w.batch_offsets, w.voxel_size, w.bucket_cap, w.scope_buckets, hash)
+
+
+@pytest.mark.parametrize("n", [1, 5, 63, 64, 65, 1023, 1024, 1025, 4097, 20000])
+def test_bucketize_small_and_ragged_sizes(n):
+    rng = np.random.default_rng(n)
+    c = wl.uniform_cube(rng, n, 1.5)
+    for hash in ("zorder_div", "xor_mod"):
+        check_bucketize(c, None, 0.05, 64, 4, hash)
+
+
+def test_bucketize_empty_input_and_empty_scans():
+    c = np.zeros((0, 3), dtype=np.float32)
+    bk = run_bucketize(c, np.array([0, 0, 0]), 0.05, 64)
+    assert bk.scan_bucket_start.cpu().numpy().tolist() == [0, 0, 0]
+    assert (bk.offsets.cpu().numpy() == 0).all()
+    rng = np.random.default_rng(20)
+    c = wl.uniform_cube(rng, 3000, 2.0)
+    check_bucketize(c, np.array([0, 0, 1000, 1000, 2500, 3000, 3000]), 0.05, 128)
+
+
+def test_bucketize_many_uneven_scans():
+    rng = np.random.default_rng(21)
+    sizes = rng.integers(1, 5000, 70)
+    bo = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    c = np.concatenate([wl.uniform_cube(rng, int(s), 3.0) + np.float32(10 * i) for i, s in enumerate(sizes)])
+    for hash in HASHES:
+        check_bucketize(c, bo, 0.04, 256, 4, hash, max_scan_points=5000)
+
+
+@pytest.mark.parametrize("n_probes", [0, 1, 3])
+def test_bucketize_fewer_probes(n_probes):
+    rng = np.random.default_rng(22)
+    c = wl.indoor_room(rng, 30000)
+    check_bucketize(c, None, 0.02, 512, 4, "zorder_div", n_probes)
+    check_bucketize(c, None, 0.02, 512, 4, "xor_div", n_probes)
+
+
+def test_bucketize_coincident_points_and_overrides():
+    c = np.full((5000, 3), 0.25, dtype=np.float32)          # everything overflows into recycle
+    check_bucketize(c, None, 1.0, 64, 4, "xor_mod")
+    rng = np.random.default_rng(23)
+    c = wl.uniform_cube(rng, 50000, 4.0)
+    check_bucketize(c, None, 0.02, 1024, 4, "zorder_div", div=777, probe_step=3)
+    check_bucketize(c, None, 0.02, 1024, 2, "xor_div", div=5)
+    check_bucketize(c, None, 0.02, 1024, 8, "zorder_mod")
+    check_bucketize(c, None, 0.02, 16, 1, "zorder_div")      # 3125 buckets of 16 in one scan
+
+
+def test_bucketize_at_the_bucket_limit():
+    rng = np.random.default_rng(24)
+    n = 8192 * 16 - 5
+    c = wl.uniform_cube(rng, n, 4.0)
+    check_bucketize(c, None, 0.02, 64, 4, "zorder_mod")      # K = 8192 buckets of 16
+
+
+def test_bucketize_is_deterministic_and_reuses_workspace():
+    w = wl.make_workload("indoor")
+    p = f3d.make_params(w.voxel_size, w.bucket_cap)
+    ws = torch.empty(f3d.workspace_bytes(w.n, 1, p), dtype=torch.uint8, device=DEV)
+    cd = dev(w.coords)
+    a = f3d.psh_bucketize(cd, None, p, ws)
+    pa = a.perm.clone()
+    ws.fill_(0xAB)                                            # stale workspace contents must not matter
+    b = f3d.psh_bucketize(cd, None, p, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(pa, b.perm)
+
+
+def test_inconsistent_batch_offsets_are_flagged_not_faulted():
+    rng = np.random.default_rng(25)
+    c = wl.uniform_cube(rng, 1000, 2.0)
+    for bo in ([0, 600, 400, 1000], [0, 500, 900], [5, 500, 1000]):
+        bk = run_bucketize(c, np.array(bo), 0.05, 64)
+        assert int(bk.scan_bucket_start[-1]) == -1
+    bk = run_bucketize(c, np.array([0, 900, 1000]), 0.05, 64, max_scan_points=800)   # a scan above the stated bound
+    assert int(bk.scan_bucket_start[-1]) == -1
+
+
+# ----------------------------------------------------------------------------- attention
+
+
+def attn_case(q, k, v, bk, ref_layout, heads, d, mode, use_perm, rows=None, shift=2, stride=2, scale=0.0):
+    """Run the GPU attention and the oracle on the same layout; compare all rows or the sampled ones."""
+    n = q.shape[0]
+    out = f3d.bucket_swin_attn(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), bk, heads, d, mode,
+                               shift, stride, use_perm, scale)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().astype(np.float64)
+    sel = None
+    if rows is not None:
+        sel = np.zeros(n, dtype=np.uint8)
+        sel[rows] = 1
+    ref = oracle.attn(q, k, v, ref_layout["perm"] if use_perm else None, ref_layout["offsets"],
+                      ref_layout["scan_bucket_start"], bk.scope_buckets, mode, heads, d, shift, stride,
+                      None if scale == 0.0 else scale, sel)
+    mask = slice(None) if rows is None else rows
+    err = np.abs(got[mask] - ref[mask])
+    assert np.isfinite(got).all()
+    assert err.max() <= ATOL, f"max-abs {err.max():.4g} (mean {err.mean():.3g})"
+    return got, err.max()
+
+
+def sample_rows(rng, ref_layout, n, count):
+    """Random rows plus the first and last rows of every scan (edge scopes, ragged tails)."""
+    rows = set(rng.integers(0, n, count).tolist())
+    off, sbs = ref_layout["offsets"], ref_layout["scan_bucket_start"]
+    for b in range(len(sbs) - 1):
+        if sbs[b + 1] > sbs[b]:
+            lo, hi = off[sbs[b]], off[sbs[b + 1]]
+            rows.update(range(lo, min(lo + 3, hi)))
+            rows.update(range(max(hi - 40, lo), hi))
+    return np.array(sorted(rows))
+
+
+def test_attention_tiny_workload_all_rows():
+    w = wl.make_workload("tiny")
+    bk, ref = check_bucketize(w.coords, w.batch_offsets, w.voxel_size, w.bucket_cap)
+    q, k, v = w.qkv()
+    for mode in ("plain", "shift", "stride"):
+        attn_case(q, k, v, bk, ref, w.heads, w.head_dim, mode, True)
+    perm = ref["perm"]
+    attn_case(q[perm], k[perm], v[perm], bk, ref, w.heads, w.head_dim, "shift", False)
+
+
+@pytest.mark.parametrize("name", ["indoor", "lidar4", "wide", "lidar8"])
+def test_attention_full_size_sampled_rows(name):
+    # the launch configuration bench.py times, on sampled query rows (each needs its whole scope in the oracle)
+    w = wl.make_workload(name)
+    bk, ref = check_bucketize(w.coords, w.batch_offsets, w.voxel_size, w.bucket_cap)
+    q, k, v = w.qkv()
+    rng = np.random.default_rng(30)
+    count = 1500 if w.channels <= 128 else 400
+    bucket_major = name == "lidar8"                      # that workload runs its layers on bucket-major features
+    if bucket_major:
+        q, k, v = q[ref["perm"]], k[ref["perm"]], v[ref["perm"]]
+    for mode in dict.fromkeys(w.modes):
+        rows = sample_rows(rng, ref, w.n, count)
+        attn_case(q, k, v, bk, ref, w.heads, w.head_dim, mode, not bucket_major, rows)
+
+
+def test_attention_indoor_plain_every_row():
+    w = wl.make_workload("indoor")
+    bk, ref = check_bucketize(w.coords, w.batch_offsets, w.voxel_size, w.bucket_cap)
+    q, k, v = w.qkv()
+    attn_case(q, k, v, bk, ref, w.heads, w.head_dim, "plain", True)
+
+
+def hand_layout(sizes_per_scan, cap, m):
+    """A Buckets object over hand-made (ragged) bucket sizes, to exercise general offsets."""
+    sizes = [s for scan in sizes_per_scan for s in scan]
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    sbs = np.concatenate([[0], np.cumsum([len(s) for s in sizes_per_scan])]).astype(np.int32)
+    n = int(off[-1])
+    kmax = n // (cap // m) + len(sizes_per_scan)
+    off_pad = np.full(max(kmax, len(sizes)) + 1, n, dtype=np.int32)
+    off_pad[:len(off)] = off
+    perm = np.random.default_rng(31).permutation(n).astype(np.int32)
+    bk = f3d.Buckets(dev(perm), None, dev(off_pad), dev(sbs), None, n, len(sizes_per_scan), cap, m, len(sizes))
+    return bk, {"perm": perm, "offsets": off, "scan_bucket_start": sbs}, n
+
+
+@pytest.mark.parametrize("d,heads", [(16, 2), (32, 2), (16, 5), (32, 3)])
+def test_attention_ragged_buckets_all_modes(d, heads):
+    # buckets of uneven size (all <= S = 64), scopes that end inside a 32-row tile, three scans
+    sizes = [[64, 64, 37, 64, 1, 64, 64, 64, 50], [17], [64, 64, 64, 64, 64, 3]]
+    bk, ref, n = hand_layout(sizes, 256, 4)
+    rng = np.random.default_rng(32)
+    q, k, v = (wl.f32_to_bf16_bits(rng.standard_normal((n, heads * d)).astype(np.float32)) for _ in range(3))
+    for mode, kw in (("plain", {}), ("shift", {"shift": 1}), ("shift", {"shift": 3}), ("stride", {"stride": 2}),
+                     ("stride", {"stride": 3})):
+        attn_case(q, k, v, bk, ref, heads, d, mode, True, **kw)
+        attn_case(q, k, v, bk, ref, heads, d, mode, False, **kw)
+
+
+def test_attention_other_scope_shapes_and_scale():
+    rng = np.random.default_rng(33)
+    for cap, m, sizes in ((32, 2, [[16] * 9 + [5]]), (512, 8, [[64] * 21 + [9]]), (2048, 1, [[2048, 2048, 700]]),
+                          (1024, 16, [[64] * 40])):
+        bk, ref, n = hand_layout(sizes, cap, m)
+        q, k, v = (wl.f32_to_bf16_bits(rng.standard_normal((n, 32)).astype(np.float32)) for _ in range(3))
+        modes = ["plain", "stride"] + (["shift"] if m > 1 else [])
+        for mode in modes:
+            attn_case(q, k, v, bk, ref, 2, 16, mode, True, shift=max(1, m // 2), scale=0.31)
+
+
+def test_attention_large_logits_stay_finite():
+    # peaked softmax: scores of order +-60 exercise the running-max rescaling
+    bk, ref, n = hand_layout([[64] * 8], 256, 4)
+    rng = np.random.default_rng(34)
+    q, k, v = (wl.f32_to_bf16_bits((rng.standard_normal((n, 32)) * s).astype(np.float32)) for s in (8.0, 8.0, 1.0))
+    attn_case(q, k, v, bk, ref, 2, 16, "plain", True)
+
+
+def test_attention_closed_forms_on_gpu():
+    bk, ref, n = hand_layout([[64] * 7 + [30]], 256, 4)
+    rng = np.random.default_rng(35)
+    q, k, v = (wl.f32_to_bf16_bits(rng.standard_normal((n, 64)).astype(np.float32)) for _ in range(3))
+    const = np.tile(v[:1], (n, 1))
+    out = f3d.bucket_swin_attn(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(const, torch.bfloat16), bk, 4, 16, "shift")
+    torch.cuda.synchronize()
+    want = wl.bf16_bits_to_f32(const)
+    assert np.abs(out.float().cpu().numpy() - want).max() <= 2.0 ** -7 * np.abs(want).max()
+
+
+# ----------------------------------------------------------------------------- unpermute, end to end
+
+
+@pytest.mark.parametrize("cols,dtype", [(64, torch.bfloat16), (256, torch.bfloat16), (3, torch.float32), (10, torch.bfloat16)])
+def test_unpermute_is_exact(cols, dtype):
+    rng = np.random.default_rng(36)
+    n = 10007
+    perm = rng.permutation(n).astype(np.int32)
+    src = torch.randn(n, cols, device=DEV).to(dtype)
+    got = f3d.unpermute(src, dev(perm))
+    torch.cuda.synchronize()
+    want = torch.empty_like(src)
+    want[dev(perm).long()] = src
+    assert torch.equal(got, want)
+    raw = src.cpu().view(torch.uint8).numpy().reshape(n, -1)
+    assert np.array_equal(got.cpu().view(torch.uint8).numpy().reshape(n, -1), oracle.unpermute(raw, perm))
+
+
+def test_end_to_end_original_order():
+    # bucketize -> attention through perm -> unpermute equals the oracle's result in input order
+    w = wl.make_workload("tiny")
+    bk, ref = check_bucketize(w.coords, w.batch_offsets, w.voxel_size, w.bucket_cap, hash="zorder_mod")
+    q, k, v = w.qkv()
+    out = f3d.bucket_swin_attn(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), bk, w.heads,
+                               w.head_dim, "shift")
+    back = f3d.unpermute(out, bk.perm)
+    torch.cuda.synchronize()
+    want = oracle.unpermute(oracle.attn(q, k, v, ref["perm"], ref["offsets"], ref["scan_bucket_start"], 4, "shift",
+                                        w.heads, w.head_dim), ref["perm"])
+    assert np.abs(back.float().cpu().numpy() - want).max() <= ATOL
