@@ -32,7 +32,8 @@ class f3d_params(ctypes.Structure):
 class Flash3DError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
-        super().__init__(f"{where}: {error_string(code)} (code {code})")
+        hip = lib().f3d_last_hip_error() if code == ERR_HIP else 0
+        super().__init__(f"{where}: {error_string(code)} (code {code}" + (f", hipError {hip})" if hip else ")"))
 
 
 _lib = None
@@ -45,6 +46,10 @@ def lib() -> ctypes.CDLL:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2412_16481_amd.build` "
                               "(there is no CPU fallback)")
+        # torch ships its own HIP runtime with the same soname as the system one. Import it first so
+        # that the library binds to the runtime that owns torch's device memory and streams; two HIP
+        # runtimes in one process do not see each other's devices.
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
         L.f3d_params_default.argtypes = [ctypes.POINTER(f3d_params), f32, i32]

@@ -184,6 +184,7 @@ int f3d_psh_bucketize(const float* coords, const int32_t* batch_offsets, int64_t
     a.left = (int32_t*)(ws + pl.o_left);
     a.leftpre = (int32_t*)(ws + pl.o_leftpre);
     a.freepre = (int32_t*)(ws + pl.o_freepre);
+    (void)hipGetLastError();  // a stale error left by an earlier, unrelated runtime call is not ours
     const hipError_t e = f3d::psh_launch(a, (hipStream_t)stream);
     return e == hipSuccess ? F3D_OK : hip_fail(e);
 }
@@ -232,6 +233,7 @@ int f3d_bucket_swin_attn(const void* q, const void* k, const void* v, const int3
     a.qblocks = (bucket_cap + f3d::ATTN_BM - 1) / f3d::ATTN_BM;
     if (slots * heads * a.qblocks > 2000000000ll) return F3D_ERR_UNSUPPORTED;
     a.n_slots = (int)slots;
+    (void)hipGetLastError();
     const hipError_t e = f3d::attn_launch(a, head_dim, (hipStream_t)stream);
     return e == hipSuccess ? F3D_OK : hip_fail(e);
 }
@@ -242,6 +244,7 @@ int f3d_unpermute(const void* src, const int32_t* perm, int64_t n, int32_t row_b
     if (n == 0) return F3D_OK;
     if (!src || !perm || !dst || src == dst) return F3D_ERR_INVALID_ARG;
     if (((uintptr_t)src | (uintptr_t)dst | (uintptr_t)perm) & 3) return F3D_ERR_BAD_ALIGNMENT;
+    (void)hipGetLastError();
     const bool wide = (row_bytes % 16 == 0) && ((((uintptr_t)src | (uintptr_t)dst) & 15) == 0);
     const long long units = n * (wide ? row_bytes / 16 : row_bytes / 4);
     long long blocks = (units + 255) / 256;
