@@ -25,6 +25,8 @@ def build(verbose: bool = False, extra=()) -> str:
            "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(HERE, "csrc"),
            # packed fp32 VALU forms are kept out of the generated code on purpose
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           # MFMA accumulators live in ordinary VGPRs (no AGPR copies around the softmax)
+           "-mllvm", "--amdgpu-mfma-vgpr-form",
            *extra, *srcs, "-o", LIB]
     res = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)

@@ -63,7 +63,7 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
     constexpr int SWZ_SHIFT = (NC == 2) ? 3 : 2;
 
     __shared__ __attribute__((aligned(16))) uint16_t sK[2][KT * D];
-    __shared__ __attribute__((aligned(16))) uint16_t sV[2][D * VSTR];
+    __shared__ __attribute__((aligned(16))) uint16_t sV[2][(D + (D == 16 ? 2 : 0)) * VSTR];
     __shared__ int seg_row0[MAXSEG];
     __shared__ int seg_pre[MAXSEG + 1];
     __shared__ int s_nseg;
@@ -189,10 +189,23 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
         }
     };
 
+    // head_dim 16: rows 16 and 17 of V^T are constants (ones -> softmax denominator, zeros -> unused rows)
+    if (D == 16) {
+        for (int i = tid; i < 2 * VSTR; i += 256) {
+            const uint16_t val = i < VSTR ? 0x3F80 : 0;
+            sV[0][D * VSTR + i] = val;
+            sV[1][D * VSTR + i] = val;
+        }
+    }
+
     f32x16 o = {0};
-    float m_run = -INFINITY, l_run = 0.f;
+    float m_ref = -INFINITY;   // reference maximum the exponentials are taken against (scaled log2 units)
+    float l_run = 0.f;
     const float cl2 = a.c_log2;
     const int nst = (ng + KT - 1) / KT;
+    // this lane's row of V^T: a head dim, or the ones row, or the zeros row
+    const int vrow = (D == 16) ? min(l32, 17) : l32;
+    const int voff = vrow * VSTR + 8 * hf;
 
     load_stage(0);
     store_stage(0);
@@ -201,8 +214,10 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
     for (int st = 0; st < nst; ++st) {
         const int buf = st & 1;
         if (st + 1 < nst) load_stage(st + 1);
+        const uint16_t* kbuf = sK[buf];
+        const uint16_t* vbuf = sV[buf] + voff;
 
-#pragma unroll 1
+#pragma unroll 2
         for (int t4 = 0; t4 < KT / 32; ++t4) {
             const int kbase = st * KT + t4 * 32;
             if (kbase >= ng) break;
@@ -214,9 +229,13 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
                 const int c = 2 * ks + hf;
                 const int cs = c ^ ((kk >> SWZ_SHIFT) & (NC - 1));
                 U4 kf;
-                kf.u = *reinterpret_cast<const uint4*>(&sK[buf][kk * D + cs * 8]);
+                kf.u = *reinterpret_cast<const uint4*>(&kbuf[kk * D + cs * 8]);
                 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.b, qf[ks].b, s, 0, 0, 0);
             }
+            // V^T fragments for both halves of the tile (issued early, consumed after the exponentials)
+            U4 vf0, vf1;
+            vf0.u = *reinterpret_cast<const uint4*>(&vbuf[t4 * 32]);
+            vf1.u = *reinterpret_cast<const uint4*>(&vbuf[t4 * 32 + 16]);
             if (kbase + 32 > ng) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
@@ -224,38 +243,43 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
                     if (key >= ng) s[r] = -INFINITY;
                 }
             }
-            float mx = s[0];
+            float mx = fmaxf(fmaxf(s[0], s[1]), s[2]);
 #pragma unroll
-            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run, mx * cl2);
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-            m_run = m_new;
+            for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
+            mx = fmaxf(mx, s[15]);
+            {   // both half-waves hold keys of the same query: share the maximum
+                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_int(mx), __float_as_int(mx), false, false);
+                mx = fmaxf(__int_as_float(sw[0]), __int_as_float(sw[1]));
+            }
+            mx *= cl2;
+            // Move the reference maximum only when a score exceeds it by more than 2^8: the exponentials
+            // stay below 256 (exact range in fp32 and bf16), and the rescaling of O is almost never needed.
+            if (__builtin_amdgcn_ballot_w64(mx > m_ref + 8.0f)) {
+                const float m_new = fmaxf(m_ref, mx);
+                const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+                m_ref = m_new;
+                constexpr int NO = (D == 16) ? 9 : 16;
+#pragma unroll
+                for (int r = 0; r < NO; ++r) o[r] *= alpha;
+                if (D == 32) l_run *= alpha;
+            }
             float p[16];
-            float psum = 0.f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                p[r] = __builtin_amdgcn_exp2f(s[r] * cl2 - m_new);
-                if (D == 32) psum += p[r];
+            for (int r = 0; r < 16; ++r) p[r] = __builtin_amdgcn_exp2f(s[r] * cl2 - m_ref);
+            if (D == 32) {
+                float psum = (p[0] + p[1]) + (p[2] + p[3]);
+#pragma unroll
+                for (int r = 4; r < 16; r += 4) psum += (p[r] + p[r + 1]) + (p[r + 2] + p[r + 3]);
+                l_run += psum;
             }
-            if (D == 32) l_run = l_run * alpha + psum;
-            constexpr int NO = (D == 16) ? 9 : 16;
+            union { uint32_t u[4]; bf16x8 b; } pb0, pb1;
 #pragma unroll
-            for (int r = 0; r < NO; ++r) o[r] *= alpha;
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                union { uint32_t u[4]; bf16x8 b; } pb;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) pb.u[e] = pack_bf16(p[8 * t + 2 * e], p[8 * t + 2 * e + 1]);
-                U4 vf;
-                const int dim = (D == 16) ? (l32 & 15) : l32;
-                vf.u = *reinterpret_cast<const uint4*>(&sV[buf][dim * VSTR + t4 * 32 + 16 * t + 8 * hf]);
-                if (D == 16) {
-                    if (l32 == 16) vf.u = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
-                    if (l32 > 16) vf.u = make_uint4(0, 0, 0, 0);
-                }
-                o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.b, pb.b, o, 0, 0, 0);
+            for (int e = 0; e < 4; ++e) {
+                pb0.u[e] = pack_bf16(p[2 * e], p[2 * e + 1]);
+                pb1.u[e] = pack_bf16(p[8 + 2 * e], p[8 + 2 * e + 1]);
             }
+            o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf0.b, pb0.b, o, 0, 0, 0);
+            o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf1.b, pb1.b, o, 0, 0, 0);
         }
 
         if (st + 1 < nst) store_stage(buf ^ 1);
