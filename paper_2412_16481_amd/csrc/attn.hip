@@ -14,6 +14,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "attn.h"
 
 namespace f3d {
@@ -198,101 +200,143 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
         }
     }
 
-    f32x16 o = {0};
-    float m_ref = -INFINITY;   // reference maximum the exponentials are taken against (scaled log2 units)
-    float l_run = 0.f;
-    const float cl2 = a.c_log2;
+    // The query fragment is pre-multiplied by softmax_scale*log2(e) and split into a bf16 head and a bf16
+    // remainder (q*c = hi + lo up to 2^-17 relative), so the MFMA delivers the scaled score directly. The
+    // vector ALU is the busy unit of this kernel, the matrix core is not: one more MFMA per tile is cheaper
+    // than 16 multiplies.
+    U4 qhi[KS], qlo[KS];
+    {
+        const float cl2 = a.c_log2;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t w2 = (&qf[ks].u.x)[e];
+                const float x0 = __uint_as_float(w2 << 16) * cl2, x1 = __uint_as_float(w2 & 0xFFFF0000u) * cl2;
+                const uint32_t h = pack_bf16(x0, x1);
+                const float r0 = x0 - __uint_as_float(h << 16), r1 = x1 - __uint_as_float(h & 0xFFFF0000u);
+                (&qhi[ks].u.x)[e] = h;
+                (&qlo[ks].u.x)[e] = pack_bf16(r0, r1);
+            }
+        }
+    }
+
     const int nst = (ng + KT - 1) / KT;
     // this lane's row of V^T: a head dim, or the ones row, or the zeros row
     const int vrow = (D == 16) ? min(l32, 17) : l32;
     const int voff = vrow * VSTR + 8 * hf;
+    const uint32_t ones2 = 0x3F803F80u;
 
-    load_stage(0);
-    store_stage(0);
-    __syncthreads();
+    f32x16 o;
+    float l_run, den;
 
-    for (int st = 0; st < nst; ++st) {
-        const int buf = st & 1;
-        if (st + 1 < nst) load_stage(st + 1);
-        const uint16_t* kbuf = sK[buf];
-        const uint16_t* vbuf = sV[buf] + voff;
-
-#pragma unroll 2
-        for (int t4 = 0; t4 < KT / 32; ++t4) {
-            const int kbase = st * KT + t4 * 32;
-            if (kbase >= ng) break;
-            // S^T tile: rows = 32 keys, cols = 32 queries
-            f32x16 s = {0};
-            const int kk = t4 * 32 + l32;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const int c = 2 * ks + hf;
-                const int cs = c ^ ((kk >> SWZ_SHIFT) & (NC - 1));
-                U4 kf;
-                kf.u = *reinterpret_cast<const uint4*>(&kbuf[kk * D + cs * 8]);
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.b, qf[ks].b, s, 0, 0, 0);
-            }
-            // V^T fragments for both halves of the tile (issued early, consumed after the exponentials)
-            U4 vf0, vf1;
-            vf0.u = *reinterpret_cast<const uint4*>(&vbuf[t4 * 32]);
-            vf1.u = *reinterpret_cast<const uint4*>(&vbuf[t4 * 32 + 16]);
-            if (kbase + 32 > ng) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = kbase + 8 * (r >> 2) + 4 * hf + (r & 3);
-                    if (key >= ng) s[r] = -INFINITY;
-                }
-            }
-            float mx = fmaxf(fmaxf(s[0], s[1]), s[2]);
-#pragma unroll
-            for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
-            mx = fmaxf(mx, s[15]);
-            {   // both half-waves hold keys of the same query: share the maximum
-                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_int(mx), __float_as_int(mx), false, false);
-                mx = fmaxf(__int_as_float(sw[0]), __int_as_float(sw[1]));
-            }
-            mx *= cl2;
-            // Move the reference maximum only when a score exceeds it by more than 2^8: the exponentials
-            // stay below 256 (exact range in fp32 and bf16), and the rescaling of O is almost never needed.
-            if (__builtin_amdgcn_ballot_w64(mx > m_ref + 8.0f)) {
-                const float m_new = fmaxf(m_ref, mx);
-                const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
-                m_ref = m_new;
-                constexpr int NO = (D == 16) ? 9 : 16;
-#pragma unroll
-                for (int r = 0; r < NO; ++r) o[r] *= alpha;
-                if (D == 32) l_run *= alpha;
-            }
-            float p[16];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) p[r] = __builtin_amdgcn_exp2f(s[r] * cl2 - m_ref);
-            if (D == 32) {
-                float psum = (p[0] + p[1]) + (p[2] + p[3]);
-#pragma unroll
-                for (int r = 4; r < 16; r += 4) psum += (p[r] + p[r + 1]) + (p[r + 2] + p[r + 3]);
-                l_run += psum;
-            }
-            union { uint32_t u[4]; bf16x8 b; } pb0, pb1;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                pb0.u[e] = pack_bf16(p[2 * e], p[2 * e + 1]);
-                pb1.u[e] = pack_bf16(p[8 + 2 * e], p[8 + 2 * e + 1]);
-            }
-            o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf0.b, pb0.b, o, 0, 0, 0);
-            o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf1.b, pb1.b, o, 0, 0, 0);
-        }
-
-        if (st + 1 < nst) store_stage(buf ^ 1);
+    // One sweep over the keys of the scope. ROBUST == false is the optimistic sweep: softmax taken against
+    // the fixed reference 0, i.e. p = 2^score with no running maximum at all. It is exact (softmax does not
+    // depend on the reference) as long as the denominator stays well inside the fp32 range, which is checked
+    // afterwards; scores beyond about +-55 (natural log units) fail the check and the workgroup repeats the
+    // sweep with ROBUST == true, the usual running-maximum form.
+    auto sweep = [&](auto robust_tag) {
+        constexpr bool ROBUST = decltype(robust_tag)::value;
+        o = f32x16{0};
+        l_run = 0.f;
+        float m_ref = 0.f;
+        bool first = true;
+        load_stage(0);
+        store_stage(0);
         __syncthreads();
+        for (int st = 0; st < nst; ++st) {
+            const int buf = st & 1;
+            if (st + 1 < nst) load_stage(st + 1);
+            const uint16_t* kbuf = sK[buf];
+            const uint16_t* vbuf = sV[buf] + voff;
+#pragma unroll 2
+            for (int t4 = 0; t4 < KT / 32; ++t4) {
+                const int kbase = st * KT + t4 * 32;
+                if (kbase >= ng) break;
+                // S^T tile (rows = 32 keys, cols = 32 queries), scaled to log2 units
+                f32x16 s = {0};
+                const int kk = t4 * 32 + l32;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const int c = 2 * ks + hf;
+                    const int cs = c ^ ((kk >> SWZ_SHIFT) & (NC - 1));
+                    U4 kf;
+                    kf.u = *reinterpret_cast<const uint4*>(&kbuf[kk * D + cs * 8]);
+                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.b, qhi[ks].b, s, 0, 0, 0);
+                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.b, qlo[ks].b, s, 0, 0, 0);
+                }
+                U4 vf0, vf1;
+                vf0.u = *reinterpret_cast<const uint4*>(&vbuf[t4 * 32]);
+                vf1.u = *reinterpret_cast<const uint4*>(&vbuf[t4 * 32 + 16]);
+                if (kbase + 32 > ng) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = kbase + 8 * (r >> 2) + 4 * hf + (r & 3);
+                        if (key >= ng) s[r] = -INFINITY;
+                    }
+                }
+                if (ROBUST) {
+                    float mx = fmaxf(fmaxf(s[0], s[1]), s[2]);
+#pragma unroll
+                    for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
+                    mx = fmaxf(mx, s[15]);
+                    {   // both half-waves hold keys of the same query: share the maximum
+                        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_int(mx), __float_as_int(mx), false, false);
+                        mx = fmaxf(__int_as_float(sw[0]), __int_as_float(sw[1]));
+                    }
+                    // the reference follows the maximum only when a score exceeds it by more than 2^8 (the first
+                    // tile sets it): exponentials stay below 256 and O is rescaled rarely
+                    if (first || __builtin_amdgcn_ballot_w64(mx > m_ref + 8.0f)) {
+                        const float m_new = first ? mx : fmaxf(mx, m_ref);
+                        first = false;
+                        const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+                        m_ref = m_new;
+                        constexpr int NO = (D == 16) ? 9 : 16;
+#pragma unroll
+                        for (int r = 0; r < NO; ++r) o[r] *= alpha;
+                        if (D == 32) l_run *= alpha;
+                    }
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) s[r] -= m_ref;
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(s[r]);
+                union { uint32_t u[4]; bf16x8 b; } pb0, pb1;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    pb0.u[e] = pack_bf16(s[2 * e], s[2 * e + 1]);
+                    pb1.u[e] = pack_bf16(s[8 + 2 * e], s[8 + 2 * e + 1]);
+                }
+                if (D == 32) {   // denominator from the rounded probabilities, two per instruction
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        l_run = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<bf16x2*>(&pb0.u[e]),
+                                                                *reinterpret_cast<const bf16x2*>(&ones2), l_run, false);
+                        l_run = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<bf16x2*>(&pb1.u[e]),
+                                                                *reinterpret_cast<const bf16x2*>(&ones2), l_run, false);
+                    }
+                }
+                o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf0.b, pb0.b, o, 0, 0, 0);
+                o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf1.b, pb1.b, o, 0, 0, 0);
+            }
+            if (st + 1 < nst) store_stage(buf ^ 1);
+            __syncthreads();
+        }
+        if (D == 16) {
+            den = __shfl(o[8], l32, 64);       // row 16 of O^T (sum of probabilities) lives in the lower half-wave
+        } else {
+            den = l_run + __shfl_xor(l_run, 32, 64);
+        }
+    };
+
+    sweep(std::false_type{});
+    {
+        // 2^-40 < den < 2^80: no exponential overflowed, and the largest one is far above the flush-to-zero range
+        const bool bad = (xq < ng) && !(den > 9.094947e-13f && den < 1.2089258e24f);
+        if (__syncthreads_or(bad)) sweep(std::true_type{});
     }
 
     // ---- epilogue: divide by the softmax denominator, round to bf16, store at the query's own row
-    float den;
-    if (D == 16) {
-        den = __shfl(o[8], l32, 64);       // row 16 of O^T lives in the lower half-wave
-    } else {
-        den = l_run + __shfl_xor(l_run, 32, 64);
-    }
     if (xq < ng) {
         const float inv = 1.0f / den;
         int s = 0;
