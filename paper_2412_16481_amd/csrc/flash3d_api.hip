@@ -29,7 +29,7 @@ struct Plan {
     long long chunks;
     size_t bytes;
     // offsets (bytes) of the workspace arrays
-    size_t o_status, o_p0, o_c0, o_mm, o_cnt, o_cnt2, o_hist, o_key, o_left, o_leftpre, o_freepre, o_inv, o_rc;
+    size_t o_status, o_p0, o_c0, o_mm, o_cnt, o_cnt2, o_hist, o_key, o_left, o_leftpre, o_freepre, o_inv, o_rc, o_cfg, o_done, o_ci;
 };
 
 int check_params(int64_t n, int32_t n_scans, const f3d_params* p)
@@ -70,12 +70,19 @@ void make_plan(int64_t n, int32_t n_scans, const f3d_params* p, Plan* pl)
     pl->o_p0 = take((size_t)(n_scans + 1) * 4);
     pl->o_c0 = take((size_t)(n_scans + 1) * 4);
     pl->o_mm = take((size_t)n_scans * 8 * 4);
+    pl->o_cfg = take((size_t)n_scans * 128);
+    pl->o_done = take((size_t)n_scans * 4);
+    pl->o_ci = take((size_t)(n / 2048 + n_scans) * 32);
     pl->o_cnt = take((size_t)(pl->max_buckets + 1) * 4);
     pl->o_cnt2 = take((size_t)(pl->max_buckets + 1) * 4);
     pl->o_freepre = take((size_t)(pl->max_buckets + 1) * 4);
     pl->o_left = take((size_t)pl->chunks * 4);
     pl->o_leftpre = take((size_t)pl->chunks * 4);
-    pl->o_hist = take((size_t)pl->chunks * pl->kcap * 4);
+    {
+        size_t hb = (size_t)pl->chunks * pl->kcap * 4;
+        const size_t fb = f3d::psh_fast_matrix_bytes(n, n_scans, pl->kcap);
+        pl->o_hist = take(hb > fb ? hb : fb);
+    }
     pl->o_key = take((size_t)n * 4);
     pl->o_inv = take((size_t)n * 4);
     pl->bytes = at;
@@ -184,8 +191,12 @@ int f3d_psh_bucketize(const float* coords, const int32_t* batch_offsets, int64_t
     a.left = (int32_t*)(ws + pl.o_left);
     a.leftpre = (int32_t*)(ws + pl.o_leftpre);
     a.freepre = (int32_t*)(ws + pl.o_freepre);
+    a.cfg = (void*)(ws + pl.o_cfg);
+    a.done = (int32_t*)(ws + pl.o_done);
+    a.chunk_info = (int4*)(ws + pl.o_ci);
     (void)hipGetLastError();  // a stale error left by an earlier, unrelated runtime call is not ours
-    const hipError_t e = f3d::psh_launch(a, (hipStream_t)stream);
+    const hipError_t e = f3d::psh_fast_eligible(pl.max_scan_points, pl.kcap) ? f3d::psh_fast_launch(a, (hipStream_t)stream)
+                                                                             : f3d::psh_launch(a, (hipStream_t)stream);
     return e == hipSuccess ? F3D_OK : hip_fail(e);
 }
 

@@ -23,6 +23,7 @@ struct PshArgs {
     int div;
     int step;
     int kcap;    // pitch of the count matrix = most buckets a scan may have
+    int chunk;   // points per workgroup chunk
     long long max_scan_points;
     int max_buckets;
     // outputs
@@ -43,8 +44,16 @@ struct PshArgs {
     int32_t* left;     // [chunks] leftovers per chunk
     int32_t* leftpre;  // [chunks]
     int32_t* freepre;  // [max_buckets]
+    void* cfg;         // [n_scans] per-scan hash settings (fast path)
+    int4* chunk_info;  // [chunks][2] {scan, chunk in scan, chunks of scan, first point}, {end point, first bucket, buckets, first chunk}; null = not wanted
+    int n_chunks_ub;   // rows of chunk_info
+    int32_t* done;     // [n_scans] workgroups of a scan that finished the bounding box (fast path)
 };
 
-hipError_t psh_launch(const PshArgs& args, hipStream_t stream);
+hipError_t psh_launch(const PshArgs& args, hipStream_t stream);       // any size
+hipError_t psh_fast_launch(const PshArgs& args, hipStream_t stream);  // small count matrix
+bool psh_fast_eligible(long long max_scan_points, int kcap);
+size_t psh_fast_matrix_bytes(long long n, int n_scans, int kcap);
+__global__ void k_psh_meta(PshArgs a);
 
 }  // namespace f3d

@@ -14,150 +14,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "psh.h"
+#include "psh_common.h"
 
 namespace f3d {
-
-namespace {
-
-constexpr uint32_t KEY_PLACED = 0xFFFFFFFFu;
-constexpr int LR_BITS = 12;  // local rank inside a chunk < CHUNK <= 4096
-
-__device__ __forceinline__ int batch_off(const PshArgs& a, int b)
-{
-    if (a.batch_offsets) return a.batch_offsets[b];
-    return b == 0 ? 0 : a.n;
-}
-
-// order-preserving map binary32 -> uint32 (so that integer atomicMin/Max give the float min/max)
-__device__ __forceinline__ uint32_t f2ord(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-__device__ __forceinline__ float ord2f(uint32_t k)
-{
-    return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
-}
-
-// spread the low 21 bits of v so that bit k lands at bit 3k
-__device__ __forceinline__ uint64_t spread3(uint32_t v)
-{
-    uint64_t x = v & 0x1FFFFFu;
-    x = (x | (x << 32)) & 0x001F00000000FFFFull;
-    x = (x | (x << 16)) & 0x001F0000FF0000FFull;
-    x = (x | (x << 8)) & 0x100F00F00F00F00Full;
-    x = (x | (x << 4)) & 0x10C30C30C30C30C3ull;
-    x = (x | (x << 2)) & 0x1249249249249249ull;
-    return x;
-}
-__device__ __forceinline__ uint64_t morton3(int x, int y, int z)
-{
-    return spread3((uint32_t)x) | (spread3((uint32_t)y) << 1) | (spread3((uint32_t)z) << 2);
-}
-
-__device__ __forceinline__ int bit_width64(uint64_t v) { return v ? 64 - __clzll((long long)v) : 0; }
-
-// per-scan hash setting, derived from the scan's bounding box by every workgroup that needs it
-struct ScanCfg {
-    float mn[3];
-    int vmax[3];
-    unsigned long long D;
-    int step;
-    int K;     // buckets of the scan
-    int p0;    // first point
-    int nb;    // points
-    int kb0;   // first bucket (global index)
-    int lastcap;
-};
-
-__device__ __forceinline__ int voxel_of(float c, float mn, float inv)
-{
-    // three separate binary32 operations; the intrinsics forbid contraction into an fma
-    float f = floorf(__fmul_rn(__fsub_rn(c, mn), inv));
-    int q = f >= (float)F3D_VOXEL_MAX ? F3D_VOXEL_MAX : (int)f;
-    return q < 0 ? 0 : q;
-}
-
-__device__ __forceinline__ int hash_bucket(int hash, int x, int y, int z, const ScanCfg& c)
-{
-    unsigned long long code;
-    if (hash == 0 || hash == 1)
-        code = (unsigned long long)((uint32_t)x ^ (uint32_t)y ^ (uint32_t)z);
-    else
-        code = morton3(x, y, z);
-    if (hash == 0 || hash == 2) return (int)(code % (unsigned long long)c.K);
-    unsigned long long q = code / c.D;
-    return (int)(q < (unsigned long long)c.K ? q : (unsigned long long)(c.K - 1));
-}
-
-// largest b in [0, n_scans) with start[b] <= x, given start[0] <= x < start[n_scans]
-__device__ __forceinline__ int find_scan(const int* start, int n_scans, int x)
-{
-    int lo = 0, hi = n_scans;
-    while (hi - lo > 1) {
-        int mid = (lo + hi) >> 1;
-        if (start[mid] <= x) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
-__device__ void load_cfg(const PshArgs& a, int b, ScanCfg& c)
-{
-    c.p0 = a.scan_p0[b];
-    c.nb = a.scan_p0[b + 1] - c.p0;
-    c.kb0 = a.sbs[b];
-    c.K = a.sbs[b + 1] - c.kb0;
-    c.lastcap = c.nb - (c.K - 1) * a.S;
-    int vm = 0;
-    for (int ax = 0; ax < 3; ++ax) {
-        c.mn[ax] = ord2f(a.mm[b * 8 + ax]);
-        float mx = ord2f(a.mm[b * 8 + 4 + ax]);
-        c.vmax[ax] = voxel_of(mx, c.mn[ax], a.inv_voxel);  // the voxel map is monotone, so this is max v
-        vm = max(vm, c.vmax[ax]);
-    }
-    int nbits = max(1, bit_width64((unsigned long long)vm));
-    unsigned long long D = 1;
-    if (a.hash == 1) D = ((1ull << nbits) - 1) / (unsigned long long)c.K + 1;
-    if (a.hash == 3) D = morton3(c.vmax[0], c.vmax[1], c.vmax[2]) / (unsigned long long)c.K + 1;
-    if (a.div > 0) D = (unsigned long long)a.div;
-    c.D = D;
-    long long step = 1;
-    if (a.hash == 1) step = (long long)(D > (unsigned long long)F3D_VOXEL_MAX ? (unsigned long long)F3D_VOXEL_MAX : D);
-    if (a.hash == 3) step = 1ll << ((bit_width64(D) + 2) / 3);
-    if (a.step > 0) step = a.step;
-    c.step = (int)step;
-}
-
-__device__ __forceinline__ int wave_incl_scan(int v, int lane)
-{
-    for (int d = 1; d < 64; d <<= 1) {
-        int t = __shfl_up(v, d, 64);
-        if (lane >= d) v += t;
-    }
-    return v;
-}
-
-// exclusive scan of one value per thread over a 1024-thread block; returns the prefix, *total = block sum
-__device__ int block_excl_scan(int v, int* total, int* lds /*[17]*/)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int inc = wave_incl_scan(v, lane);
-    if (lane == 63) lds[wave] = inc;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int run = 0;
-        for (int w = 0; w < (int)(blockDim.x >> 6); ++w) { int t = lds[w]; lds[w] = run; run += t; }
-        lds[16] = run;
-    }
-    __syncthreads();
-    int res = inc - v + lds[wave];
-    *total = lds[16];
-    __syncthreads();
-    return res;
-}
-
-}  // namespace
 
 // ------------------------------------------------------------------------------------------------
 // one workgroup: per-scan tables (points, buckets, chunks), offsets[], counters, bounding-box init
@@ -182,7 +41,7 @@ __global__ __launch_bounds__(1024) void k_psh_meta(PshArgs a)
             if (!ok) bad = 1;
             if (ok) {
                 K = (int)((nb + a.S - 1) / a.S);
-                c = (int)((nb + PSH_CHUNK - 1) / PSH_CHUNK);
+                c = (int)((nb + a.chunk - 1) / a.chunk);
             }
         }
         int ktot, ctot;
@@ -196,6 +55,7 @@ __global__ __launch_bounds__(1024) void k_psh_meta(PshArgs a)
                 a.mm[b * 8 + ax] = 0xFFFFFFFFu;
                 a.mm[b * 8 + 4 + ax] = 0u;
             }
+            a.done[b] = 0;
         }
         kcarry += ktot;
         ccarry += ctot;
@@ -221,6 +81,20 @@ __global__ __launch_bounds__(1024) void k_psh_meta(PshArgs a)
         }
     }
     for (int j = kcarry + tid; j <= a.max_buckets; j += 1024) a.offsets[j] = a.n;
+    // chunk table: everything a workgroup needs to find its points, in one load
+    if (a.chunk_info) {
+        for (int b = 0; b < a.n_scans; ++b) {
+            const int p0 = a.scan_p0[b], p1 = a.scan_p0[b + 1];
+            const int kb0 = a.sbs[b], K = a.sbs[b + 1] - kb0;
+            const int c0 = a.scan_c0[b], nc = a.scan_c0[b + 1] - c0;
+            for (int lc = tid; lc < nc; lc += 1024) {
+                const int begin = p0 + lc * a.chunk;
+                a.chunk_info[2 * (c0 + lc)] = make_int4(b, lc, nc, begin);
+                a.chunk_info[2 * (c0 + lc) + 1] = make_int4(min(begin + a.chunk, p1), kb0, K, c0);
+            }
+        }
+        for (int c = ccarry + tid; c < a.n_chunks_ub; c += 1024) a.chunk_info[2 * c] = make_int4(-1, 0, 0, 0);
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -280,7 +154,7 @@ __global__ __launch_bounds__(PSH_THREADS) void k_psh_step(PshArgs a, int r)
     if (chunk >= a.scan_c0[a.n_scans]) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = find_scan(a.scan_c0, a.n_scans, chunk);
-    if (tid == 0) { load_cfg(a, b, cfg); placed_ct = 0; }
+    if (tid == 0) { compute_cfg(a, b, a.mm + b * 8, cfg); placed_ct = 0; }
     const int kwords = (a.kcap + 1) >> 1;
     int* pre = smem;                              // [kcap]
     uint32_t* wh = (uint32_t*)(smem + a.kcap);    // [PSH_WAVES][kwords], two 16-bit counters per word
@@ -327,13 +201,7 @@ __global__ __launch_bounds__(PSH_THREADS) void k_psh_step(PshArgs a, int r)
             int x = voxel_of(c[0], cfg.mn[0], a.inv_voxel);
             int y = voxel_of(c[1], cfg.mn[1], a.inv_voxel);
             int z = voxel_of(c[2], cfg.mn[2], a.inv_voxel);
-            if (r > 0) {
-                const int ax = (r - 1) >> 1;
-                const long long d = ((r - 1) & 1) ? -(long long)cfg.step : (long long)cfg.step;
-                if (ax == 0) x = (int)min(max((long long)x + d, 0ll), (long long)cfg.vmax[0]);
-                if (ax == 1) y = (int)min(max((long long)y + d, 0ll), (long long)cfg.vmax[1]);
-                if (ax == 2) z = (int)min(max((long long)z + d, 0ll), (long long)cfg.vmax[2]);
-            }
+            if (r > 0) probe_voxel(r, cfg, x, y, z);
             h = hash_bucket(a.hash, x, y, z, cfg);
         }
         // lanes of this wave that contend for the same bucket, by ballots over the key bits
@@ -499,6 +367,8 @@ __global__ __launch_bounds__(PSH_THREADS) void k_psh_recycle_place(PshArgs a)
 hipError_t psh_launch(const PshArgs& args, hipStream_t stream)
 {
     PshArgs a = args;
+    a.chunk = PSH_CHUNK;
+    a.chunk_info = nullptr;  // the chunk table is sized for the other path's chunks
     k_psh_meta<<<1, 1024, 0, stream>>>(a);
     if (a.n == 0) return hipGetLastError();
     const int chunks = (int)(a.n / PSH_CHUNK) + a.n_scans;  // upper bound, surplus workgroups exit
