@@ -84,6 +84,8 @@ def main() -> int:
     ap.add_argument("--hash", default="zorder_div")
     ap.add_argument("--cpu-rows", type=int, default=-1,
                     help="query rows the oracle computes per pass (-1 = about 20 s of host work, 0 = skip)")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="also run one plain device copy of this many MiB (counter calibration for rocprofv3 --pmc runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on ONE GPU; --gpus above 1 is not supported (no collectives, no sharding)",
@@ -139,6 +141,11 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibrate_copy > 0:   # a copy of known size: FETCH_SIZE / WRITE_SIZE read against it give the scale factor
+        src_c = torch.zeros(args.calibrate_copy << 20, dtype=torch.uint8, device=dev)
+        dst_c = torch.empty_like(src_c)
+        dst_c.copy_(src_c)
+        torch.cuda.synchronize()
     all_events = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
