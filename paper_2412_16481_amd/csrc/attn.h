@@ -5,8 +5,6 @@
 
 namespace f3d {
 
-constexpr int ATTN_BM = 128;  // query rows per workgroup
-
 struct AttnArgs {
     const uint16_t* q;
     const uint16_t* k;
@@ -25,10 +23,11 @@ struct AttnArgs {
     int C;        // row pitch in elements = heads * head_dim
     float c_log2; // softmax scale * log2(e)
     int n_slots;  // scope slots over all scans (upper bound, surplus workgroups exit)
-    int qblocks;  // query blocks per scope = ceil(bucket_cap / ATTN_BM)
+    int qblocks;  // query blocks per scope = ceil(bucket_cap / attn_block_rows(...))
     int extra;    // spare slots per scan: 2 (plain, shift) or stride + 1
 };
 
-hipError_t attn_launch(const AttnArgs& a, int head_dim, hipStream_t stream);
+int attn_block_rows(int head_dim, long long slots, int heads, int bucket_cap);   // query rows one workgroup covers
+hipError_t attn_launch(const AttnArgs& a, int head_dim, int block_rows, hipStream_t stream);
 
 }  // namespace f3d

@@ -1,16 +1,17 @@
 // Bucket-and-Swin attention forward for gfx950 (Section 4.2; Appendix "Bucket-Swin").
 //
-// One workgroup = 4 waves = 128 query rows of one (scope, head). Keys/values of the scope stream
-// through LDS in stages of 128 rows, double buffered. Which rows a stage holds is index arithmetic on
-// the bucket offsets (plain / shifted / strided scope), so regrouping costs no pass over memory.
+// One workgroup = 4 waves; a wave owns QT tiles of 32 query rows of one (scope, head), so a workgroup covers
+// 128*QT query rows. Keys/values of the scope stream through LDS in stages of 128 rows, double buffered.
+// Which rows a stage holds is index arithmetic on the bucket offsets (plain / shifted / strided scope), so
+// regrouping costs no pass over memory.
 //
-// Per 32-key tile a wave computes the TRANSPOSED score tile S^T = K Q^T with one 32x32x16 bf16 MFMA
-// per 16 head dims. In the MFMA result layout a lane then owns 16 keys of ONE query, so the running
-// max and the exponentials are per-lane work, and the fp32 result registers, rounded to bf16, already
-// are the B operand of the second MFMA O^T += V^T P^T as long as V^T is read from LDS in the matching
-// key order. No cross-lane shuffle of P, no LDS round trip.
-// For head_dim 16 the second MFMA has 16 spare output rows; row 16 multiplies P by ones, which yields
-// the softmax denominator on the matrix core instead of the vector ALU.
+// Per 32-key tile a wave computes the TRANSPOSED score tile S^T = K Q^T with 32x32x16 bf16 MFMAs. In the
+// MFMA result layout a lane then owns 16 keys of ONE query, so the exponentials are per-lane work, and the
+// fp32 result registers, rounded to bf16, already are the B operand of the second MFMA O^T += V^T P^T as
+// long as V^T is read from LDS in the matching key order. No cross-lane shuffle of P, no LDS round trip.
+// For head_dim 16 the second MFMA has 16 spare output rows; row 16 multiplies P by ones, which yields the
+// softmax denominator on the matrix core instead of the vector ALU.
+// The K and V^T fragments of a key tile are read from LDS once and used for all QT query tiles of the wave.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -27,7 +28,6 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 
-constexpr int BM = ATTN_BM;     // query rows per workgroup
 constexpr int KT = 128;         // key rows per LDS stage
 constexpr int VSTR = KT + 8;    // row pitch of V^T in LDS (elements); keeps 16-byte alignment, staggers banks
 constexpr int MAXSEG = 16;
@@ -56,13 +56,14 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
     return *reinterpret_cast<uint32_t*>(&y);
 }
 
-template <int D>
+template <int D, int QT>
 __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
 {
     constexpr int NC = D / 8;              // 16-byte chunks of one head in a row
     constexpr int KS = D / 16;             // MFMA k-steps for Q K^T
     constexpr int LPT = KT * NC / 256;     // 16-byte loads per thread per stage and tensor
     constexpr int SWZ_SHIFT = (NC == 2) ? 3 : 2;
+    constexpr int BM = 128 * QT;           // query rows per workgroup
 
     __shared__ __attribute__((aligned(16))) uint16_t sK[2][KT * D];
     __shared__ __attribute__((aligned(16))) uint16_t sV[2][(D + (D == 16 ? 2 : 0)) * VSTR];
@@ -94,8 +95,8 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
         if (a.mode == 2) {
             const int t = a.stride;
             const int full = K / (m * t), rem = K - full * m * t;
-            const int ng = full * t + min(rem, t);
-            if (g < ng) {
+            const int ngr = full * t + min(rem, t);
+            if (g < ngr) {
                 const int j0 = (g / t) * m * t + (g % t);
                 for (int i = 0; i < m; ++i) {
                     const int j = j0 + i * t;
@@ -137,40 +138,54 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
     const int ng = seg_pre[nseg];         // rows in this scope
     if (qb * BM >= ng) return;
 
-    auto row_of = [&](int x) -> int {
+    auto seg_row = [&](int x) -> int {    // bucket-major row of the x-th row of the scope
         int s = 0;
         while (s + 1 < nseg && x >= seg_pre[s + 1]) ++s;
-        int r = seg_row0[s] + (x - seg_pre[s]);
+        return seg_row0[s] + (x - seg_pre[s]);
+    };
+    auto row_of = [&](int x) -> int {     // ... and where that row's q/k/v live
+        const int r = seg_row(x);
         return a.perm ? a.perm[r] : r;
     };
 
     const size_t hoff = (size_t)head * D;
 
-    // ---- this lane's query fragment: row l32 of the wave's 32 queries, dims 8*hf + 16*ks ..
-    const int xq = qb * BM + wave * 32 + l32;
-    U4 qf[KS];
-    {
+    // ---- this lane's query fragments: row l32 of each of the wave's QT query tiles, dims 8*hf + 16*ks ..
+    U4 qf[QT][KS];
+    int orow[QT];
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+        const int xq = qb * BM + (wave * QT + t) * 32 + l32;
         const bool ok = xq < ng;
-        const size_t gr = ok ? (size_t)row_of(xq) : 0;
+        orow[t] = ok ? seg_row(xq) : -1;
+        const size_t gr = ok ? (size_t)(a.perm ? a.perm[orow[t]] : orow[t]) : 0;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            qf[ks].u = make_uint4(0, 0, 0, 0);
-            if (ok) qf[ks].u = *reinterpret_cast<const uint4*>(a.q + gr * a.C + hoff + ks * 16 + hf * 8);
+            qf[t][ks].u = make_uint4(0, 0, 0, 0);
+            if (ok) qf[t][ks].u = *reinterpret_cast<const uint4*>(a.q + gr * a.C + hoff + ks * 16 + hf * 8);
         }
     }
 
-    // ---- staging of K and V rows
+    // ---- staging of K and V rows. The row index of a staged key goes through the permutation, a load the
+    //      K/V loads depend on; it is fetched one stage earlier than the rows themselves so that no stage
+    //      starts with a dependent round trip to memory.
     U4 kreg[LPT], vreg[LPT];
-    auto load_stage = [&](int st) {
+    int rows_next[LPT];
+    auto fetch_rows = [&](int st) {
 #pragma unroll
         for (int i = 0; i < LPT; ++i) {
-            const int uidx = tid + i * 256;
-            const int kk = uidx / NC, c = uidx % NC;
-            const int x = st * KT + kk;
+            const int x = st * KT + (tid + i * 256) / NC;
+            rows_next[i] = x < ng ? row_of(x) : -1;
+        }
+    };
+    auto load_stage = [&]() {   // rows_next -> registers
+#pragma unroll
+        for (int i = 0; i < LPT; ++i) {
+            const int c = (tid + i * 256) % NC;
             kreg[i].u = make_uint4(0, 0, 0, 0);
             vreg[i].u = make_uint4(0, 0, 0, 0);
-            if (x < ng) {
-                const size_t at = (size_t)row_of(x) * a.C + hoff + c * 8;
+            if (rows_next[i] >= 0) {
+                const size_t at = (size_t)rows_next[i] * a.C + hoff + c * 8;
                 kreg[i].u = *reinterpret_cast<const uint4*>(a.k + at);
                 vreg[i].u = *reinterpret_cast<const uint4*>(a.v + at);
             }
@@ -204,19 +219,22 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
     // remainder (q*c = hi + lo up to 2^-17 relative), so the MFMA delivers the scaled score directly. The
     // vector ALU is the busy unit of this kernel, the matrix core is not: one more MFMA per tile is cheaper
     // than 16 multiplies.
-    U4 qhi[KS], qlo[KS];
+    U4 qhi[QT][KS], qlo[QT][KS];
     {
         const float cl2 = a.c_log2;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
+        for (int t = 0; t < QT; ++t) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const uint32_t w2 = (&qf[ks].u.x)[e];
-                const float x0 = __uint_as_float(w2 << 16) * cl2, x1 = __uint_as_float(w2 & 0xFFFF0000u) * cl2;
-                const uint32_t h = pack_bf16(x0, x1);
-                const float r0 = x0 - __uint_as_float(h << 16), r1 = x1 - __uint_as_float(h & 0xFFFF0000u);
-                (&qhi[ks].u.x)[e] = h;
-                (&qlo[ks].u.x)[e] = pack_bf16(r0, r1);
+            for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t w2 = (&qf[t][ks].u.x)[e];
+                    const float x0 = __uint_as_float(w2 << 16) * cl2, x1 = __uint_as_float(w2 & 0xFFFF0000u) * cl2;
+                    const uint32_t h = pack_bf16(x0, x1);
+                    const float r0 = x0 - __uint_as_float(h << 16), r1 = x1 - __uint_as_float(h & 0xFFFF0000u);
+                    (&qhi[t][ks].u.x)[e] = h;
+                    (&qlo[t][ks].u.x)[e] = pack_bf16(r0, r1);
+                }
             }
         }
     }
@@ -227,8 +245,8 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
     const int voff = vrow * VSTR + 8 * hf;
     const uint32_t ones2 = 0x3F803F80u;
 
-    f32x16 o;
-    float l_run, den;
+    f32x16 o[QT];
+    float l_run[QT], den[QT];
 
     // One sweep over the keys of the scope. ROBUST == false is the optimistic sweep: softmax taken against
     // the fixed reference 0, i.e. p = 2^score with no running maximum at all. It is exact (softmax does not
@@ -237,134 +255,176 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
     // sweep with ROBUST == true, the usual running-maximum form.
     auto sweep = [&](auto robust_tag) {
         constexpr bool ROBUST = decltype(robust_tag)::value;
-        o = f32x16{0};
-        l_run = 0.f;
-        float m_ref = 0.f;
-        bool first = true;
-        load_stage(0);
+        float m_ref[QT];
+        bool first[QT];
+#pragma unroll
+        for (int t = 0; t < QT; ++t) {
+            o[t] = f32x16{0};
+            l_run[t] = 0.f;
+            m_ref[t] = 0.f;
+            first[t] = true;
+        }
+        fetch_rows(0);
+        load_stage();
+        fetch_rows(1);
         store_stage(0);
         __syncthreads();
         for (int st = 0; st < nst; ++st) {
             const int buf = st & 1;
-            if (st + 1 < nst) load_stage(st + 1);
+            if (st + 1 < nst) {
+                load_stage();            // rows of stage st+1, fetched a stage ago
+                fetch_rows(st + 2);
+            }
             const uint16_t* kbuf = sK[buf];
             const uint16_t* vbuf = sV[buf] + voff;
 #pragma unroll 2
             for (int t4 = 0; t4 < KT / 32; ++t4) {
                 const int kbase = st * KT + t4 * 32;
                 if (kbase >= ng) break;
-                // S^T tile (rows = 32 keys, cols = 32 queries), scaled to log2 units
-                f32x16 s = {0};
                 const int kk = t4 * 32 + l32;
+                U4 kf[KS];
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
                     const int c = 2 * ks + hf;
                     const int cs = c ^ ((kk >> SWZ_SHIFT) & (NC - 1));
-                    U4 kf;
-                    kf.u = *reinterpret_cast<const uint4*>(&kbuf[kk * D + cs * 8]);
-                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.b, qhi[ks].b, s, 0, 0, 0);
-                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.b, qlo[ks].b, s, 0, 0, 0);
+                    kf[ks].u = *reinterpret_cast<const uint4*>(&kbuf[kk * D + cs * 8]);
                 }
                 U4 vf0, vf1;
                 vf0.u = *reinterpret_cast<const uint4*>(&vbuf[t4 * 32]);
                 vf1.u = *reinterpret_cast<const uint4*>(&vbuf[t4 * 32 + 16]);
-                if (kbase + 32 > ng) {
+                // S^T tiles (rows = 32 keys, cols = 32 queries), scaled to log2 units
+                f32x16 s[QT];
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int key = kbase + 8 * (r >> 2) + 4 * hf + (r & 3);
-                        if (key >= ng) s[r] = -INFINITY;
+                for (int t = 0; t < QT; ++t) {
+                    s[t] = f32x16{0};
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) {
+                        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks].b, qhi[t][ks].b, s[t], 0, 0, 0);
+                        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks].b, qlo[t][ks].b, s[t], 0, 0, 0);
                     }
                 }
-                if (ROBUST) {
-                    float mx = fmaxf(fmaxf(s[0], s[1]), s[2]);
 #pragma unroll
-                    for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
-                    mx = fmaxf(mx, s[15]);
-                    {   // both half-waves hold keys of the same query: share the maximum
-                        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_int(mx), __float_as_int(mx), false, false);
-                        mx = fmaxf(__int_as_float(sw[0]), __int_as_float(sw[1]));
+                for (int t = 0; t < QT; ++t) {
+                    if (kbase + 32 > ng) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int key = kbase + 8 * (r >> 2) + 4 * hf + (r & 3);
+                            if (key >= ng) s[t][r] = -INFINITY;
+                        }
                     }
-                    // the reference follows the maximum only when a score exceeds it by more than 2^8 (the first
-                    // tile sets it): exponentials stay below 256 and O is rescaled rarely
-                    if (first || __builtin_amdgcn_ballot_w64(mx > m_ref + 8.0f)) {
-                        const float m_new = first ? mx : fmaxf(mx, m_ref);
-                        first = false;
-                        const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
-                        m_ref = m_new;
-                        constexpr int NO = (D == 16) ? 9 : 16;
+                    if (ROBUST) {
+                        float mx = fmaxf(fmaxf(s[t][0], s[t][1]), s[t][2]);
 #pragma unroll
-                        for (int r = 0; r < NO; ++r) o[r] *= alpha;
-                        if (D == 32) l_run *= alpha;
+                        for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, s[t][r]), s[t][r + 1]);
+                        mx = fmaxf(mx, s[t][15]);
+                        {   // both half-waves hold keys of the same query: share the maximum
+                            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_int(mx), __float_as_int(mx), false, false);
+                            mx = fmaxf(__int_as_float(sw[0]), __int_as_float(sw[1]));
+                        }
+                        // the reference follows the maximum only when a score exceeds it by more than 2^8 (the first
+                        // tile sets it): exponentials stay below 256 and O is rescaled rarely
+                        if (first[t] || __builtin_amdgcn_ballot_w64(mx > m_ref[t] + 8.0f)) {
+                            const float m_new = first[t] ? mx : fmaxf(mx, m_ref[t]);
+                            first[t] = false;
+                            const float alpha = __builtin_amdgcn_exp2f(m_ref[t] - m_new);
+                            m_ref[t] = m_new;
+                            constexpr int NO = (D == 16) ? 9 : 16;
+#pragma unroll
+                            for (int r = 0; r < NO; ++r) o[t][r] *= alpha;
+                            if (D == 32) l_run[t] *= alpha;
+                        }
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) s[t][r] -= m_ref[t];
                     }
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) s[r] -= m_ref;
-                }
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(s[r]);
-                union { uint32_t u[4]; bf16x8 b; } pb0, pb1;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    pb0.u[e] = pack_bf16(s[2 * e], s[2 * e + 1]);
-                    pb1.u[e] = pack_bf16(s[8 + 2 * e], s[8 + 2 * e + 1]);
-                }
-                if (D == 32) {   // denominator from the rounded probabilities, two per instruction
+                    for (int r = 0; r < 16; ++r) s[t][r] = __builtin_amdgcn_exp2f(s[t][r]);
+                    union { uint32_t u[4]; bf16x8 b; } pb0, pb1;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        l_run = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<bf16x2*>(&pb0.u[e]),
-                                                                *reinterpret_cast<const bf16x2*>(&ones2), l_run, false);
-                        l_run = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<bf16x2*>(&pb1.u[e]),
-                                                                *reinterpret_cast<const bf16x2*>(&ones2), l_run, false);
+                        pb0.u[e] = pack_bf16(s[t][2 * e], s[t][2 * e + 1]);
+                        pb1.u[e] = pack_bf16(s[t][8 + 2 * e], s[t][8 + 2 * e + 1]);
                     }
+                    if (D == 32) {   // denominator from the rounded probabilities, two per instruction
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            l_run[t] = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<bf16x2*>(&pb0.u[e]),
+                                                                       *reinterpret_cast<const bf16x2*>(&ones2), l_run[t], false);
+                            l_run[t] = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<bf16x2*>(&pb1.u[e]),
+                                                                       *reinterpret_cast<const bf16x2*>(&ones2), l_run[t], false);
+                        }
+                    }
+                    o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf0.b, pb0.b, o[t], 0, 0, 0);
+                    o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf1.b, pb1.b, o[t], 0, 0, 0);
                 }
-                o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf0.b, pb0.b, o, 0, 0, 0);
-                o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf1.b, pb1.b, o, 0, 0, 0);
             }
             if (st + 1 < nst) store_stage(buf ^ 1);
             __syncthreads();
         }
-        if (D == 16) {
-            den = __shfl(o[8], l32, 64);       // row 16 of O^T (sum of probabilities) lives in the lower half-wave
-        } else {
-            den = l_run + __shfl_xor(l_run, 32, 64);
+#pragma unroll
+        for (int t = 0; t < QT; ++t) {
+            if (D == 16) {
+                den[t] = __shfl(o[t][8], l32, 64);   // row 16 of O^T (sum of probabilities) lives in the lower half-wave
+            } else {
+                den[t] = l_run[t] + __shfl_xor(l_run[t], 32, 64);
+            }
         }
     };
 
     sweep(std::false_type{});
     {
         // 2^-40 < den < 2^80: no exponential overflowed, and the largest one is far above the flush-to-zero range
-        const bool bad = (xq < ng) && !(den > 9.094947e-13f && den < 1.2089258e24f);
+        bool bad = false;
+#pragma unroll
+        for (int t = 0; t < QT; ++t) bad = bad || ((orow[t] >= 0) && !(den[t] > 9.094947e-13f && den[t] < 1.2089258e24f));
         if (__syncthreads_or(bad)) sweep(std::true_type{});
     }
 
     // ---- epilogue: divide by the softmax denominator, round to bf16, store at the query's own row
-    if (xq < ng) {
-        const float inv = 1.0f / den;
-        int s = 0;
-        while (s + 1 < nseg && xq >= seg_pre[s + 1]) ++s;
-        const size_t orow = (size_t)(seg_row0[s] + (xq - seg_pre[s]));   // bucket-major row, never through perm
-        uint16_t* dst = a.out + orow * a.C + hoff;
-        constexpr int NB = D / 8;
 #pragma unroll
-        for (int blk = 0; blk < NB; ++blk) {
-            uint2 pk;
-            pk.x = pack_bf16(o[4 * blk] * inv, o[4 * blk + 1] * inv);
-            pk.y = pack_bf16(o[4 * blk + 2] * inv, o[4 * blk + 3] * inv);
-            *reinterpret_cast<uint2*>(dst + 8 * blk + 4 * hf) = pk;
+    for (int t = 0; t < QT; ++t) {
+        if (orow[t] >= 0) {
+            const float inv = 1.0f / den[t];
+            uint16_t* dst = a.out + (size_t)orow[t] * a.C + hoff;   // bucket-major row, never through perm
+            constexpr int NB = D / 8;
+#pragma unroll
+            for (int blk = 0; blk < NB; ++blk) {
+                uint2 pk;
+                pk.x = pack_bf16(o[t][4 * blk] * inv, o[t][4 * blk + 1] * inv);
+                pk.y = pack_bf16(o[t][4 * blk + 2] * inv, o[t][4 * blk + 3] * inv);
+                *reinterpret_cast<uint2*>(dst + 8 * blk + 4 * hf) = pk;
+            }
         }
     }
 }
 
 }  // namespace
 
-hipError_t attn_launch(const AttnArgs& a, int head_dim, hipStream_t stream)
+// Query rows per workgroup. Two query tiles per wave share every K/V fragment read and halve the staging per
+// FLOP, but need more registers (3 instead of 5 waves per SIMD) and make fewer, longer workgroups; that pays
+// only when the launch is many times larger than what the GPU keeps resident.
+static int pick_qt(int head_dim, long long slots, int heads, int bucket_cap)
+{
+    if (head_dim != 16) return 1;
+    const long long wgs_qt1 = slots * heads * ((bucket_cap + 127) / 128);
+    return wgs_qt1 >= 16384 ? 2 : 1;
+}
+
+int attn_block_rows(int head_dim, long long slots, int heads, int bucket_cap)
+{
+    return 128 * pick_qt(head_dim, slots, heads, bucket_cap);
+}
+
+hipError_t attn_launch(const AttnArgs& a, int head_dim, int block_rows, hipStream_t stream)
 {
     long long total = (long long)a.n_slots * a.H * a.qblocks;
     total = (total + 7) / 8 * 8;
     if (total == 0) return hipSuccess;
-    if (head_dim == 16)
-        k_attn<16><<<(unsigned)total, 256, 0, stream>>>(a);
+    if (head_dim == 16 && block_rows == 256)
+        k_attn<16, 2><<<(unsigned)total, 256, 0, stream>>>(a);
+    else if (head_dim == 16)
+        k_attn<16, 1><<<(unsigned)total, 256, 0, stream>>>(a);
     else
-        k_attn<32><<<(unsigned)total, 256, 0, stream>>>(a);
+        k_attn<32, 1><<<(unsigned)total, 256, 0, stream>>>(a);
     return hipGetLastError();
 }
 

@@ -241,11 +241,12 @@ int f3d_bucket_swin_attn(const void* q, const void* k, const void* v, const int3
     a.c_log2 = scale * 1.44269504088896340736f;
     a.extra = mode == F3D_STRIDE ? stride + 1 : 2;
     const long long slots = max_buckets / scope_buckets + (long long)a.extra * n_scans + 1;
-    a.qblocks = (bucket_cap + f3d::ATTN_BM - 1) / f3d::ATTN_BM;
+    const int bm = f3d::attn_block_rows(head_dim, slots, heads, bucket_cap);
+    a.qblocks = (bucket_cap + bm - 1) / bm;
     if (slots * heads * a.qblocks > 2000000000ll) return F3D_ERR_UNSUPPORTED;
     a.n_slots = (int)slots;
     (void)hipGetLastError();
-    const hipError_t e = f3d::attn_launch(a, head_dim, (hipStream_t)stream);
+    const hipError_t e = f3d::attn_launch(a, head_dim, bm, (hipStream_t)stream);
     return e == hipSuccess ? F3D_OK : hip_fail(e);
 }
 
