@@ -27,6 +27,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int KT = 128;         // key rows per LDS stage
 constexpr int VSTR = KT + 8;    // row pitch of V^T in LDS (elements); keeps 16-byte alignment, staggers banks
@@ -47,6 +48,26 @@ __device__ __forceinline__ int find_slot_scan(const int* sbs, int n_scans, int m
         if (sbs[mid] / m + extra * mid <= slot) lo = mid; else hi = mid;
     }
     return lo;
+}
+
+// Position inside a scope -> bucket-major row. A scope is up to m runs of rows (one per bucket).
+struct SegMap {
+    int nseg, d0, d1, d2, d3, p1, p2, p3;
+};
+
+__device__ __forceinline__ int seg_row_of(const SegMap sm, const int* seg_pre, const int* seg_row0, int x)
+{
+    if (sm.nseg == 1) return sm.d0 + x;
+    if (sm.nseg <= 4) {
+        int d = sm.d0;
+        d = x >= sm.p1 ? sm.d1 : d;
+        d = x >= sm.p2 ? sm.d2 : d;
+        d = x >= sm.p3 ? sm.d3 : d;
+        return x + d;
+    }
+    int s = 0;
+    while (s + 1 < sm.nseg && x >= seg_pre[s + 1]) ++s;
+    return seg_row0[s] + (x - seg_pre[s]);
 }
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
@@ -138,17 +159,23 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
     const int ng = seg_pre[nseg];         // rows in this scope
     if (qb * BM >= ng) return;
 
-    auto seg_row = [&](int x) -> int {    // bucket-major row of the x-th row of the scope
-        int s = 0;
-        while (s + 1 < nseg && x >= seg_pre[s + 1]) ++s;
-        return seg_row0[s] + (x - seg_pre[s]);
-    };
-    auto row_of = [&](int x) -> int {     // ... and where that row's q/k/v live
-        const int r = seg_row(x);
-        return a.perm ? a.perm[r] : r;
+    // Up to four segments (the usual scope of four buckets) are kept in scalar registers as (first position,
+    // row minus position) pairs, so mapping a position to its row is a few compares and no LDS traffic.
+    constexpr int BIG = 0x7FFFFFFF;
+    const int d0 = __builtin_amdgcn_readfirstlane(seg_row0[0]);
+    const int p1 = __builtin_amdgcn_readfirstlane(nseg > 1 ? seg_pre[1] : BIG);
+    const int p2 = __builtin_amdgcn_readfirstlane(nseg > 2 ? seg_pre[2] : BIG);
+    const int p3 = __builtin_amdgcn_readfirstlane(nseg > 3 ? seg_pre[3] : BIG);
+    const int d1 = __builtin_amdgcn_readfirstlane(nseg > 1 ? seg_row0[1] - seg_pre[1] : 0);
+    const int d2 = __builtin_amdgcn_readfirstlane(nseg > 2 ? seg_row0[2] - seg_pre[2] : 0);
+    const int d3 = __builtin_amdgcn_readfirstlane(nseg > 3 ? seg_row0[3] - seg_pre[3] : 0);
+    const SegMap sm{nseg, d0, d1, d2, d3, p1, p2, p3};
+    auto seg_row = [sm](int x) __attribute__((always_inline)) -> int {
+        return seg_row_of(sm, seg_pre, seg_row0, x);
     };
 
     const size_t hoff = (size_t)head * D;
+    const uint32_t row_bytes = (uint32_t)a.C * 2u;
 
     // ---- this lane's query fragments: row l32 of each of the wave's QT query tiles, dims 8*hf + 16*ks ..
     U4 qf[QT][KS];
@@ -168,41 +195,58 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
 
     // ---- staging of K and V rows. The row index of a staged key goes through the permutation, a load the
     //      K/V loads depend on; it is fetched one stage earlier than the rows themselves so that no stage
-    //      starts with a dependent round trip to memory.
-    U4 kreg[LPT], vreg[LPT];
-    int rows_next[LPT];
-    auto fetch_rows = [&](int st) {
+    //      starts with a dependent round trip to memory. Positions past the end of the scope fetch its last
+    //      row again instead of zeros: their scores are masked, so all they must be is finite wherever the
+    //      scope's own rows are, and no lane leaves the common path.
+    u32x4 kreg[LPT], vreg[LPT];
+    uint32_t rows_next[LPT];
+    const char* kthr[LPT];   // this thread's 16-byte column of the K / V matrices
+    const char* vthr[LPT];
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+        const int c = (tid + i * 256) % NC;
+        kthr[i] = reinterpret_cast<const char*>(a.k + hoff + c * 8);
+        vthr[i] = reinterpret_cast<const char*>(a.v + hoff + c * 8);
+    }
+    auto fetch_rows = [&](int st) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < LPT; ++i) {
-            const int x = st * KT + (tid + i * 256) / NC;
-            rows_next[i] = x < ng ? row_of(x) : -1;
+            const int x = min(st * KT + (tid + i * 256) / NC, ng - 1);
+            const uint32_t r = (uint32_t)seg_row(x);
+            rows_next[i] = a.perm ? (uint32_t)a.perm[r] : r;
         }
     };
-    auto load_stage = [&]() {   // rows_next -> registers
+    auto load_stage = [&]() __attribute__((always_inline)) {   // rows_next -> registers
 #pragma unroll
         for (int i = 0; i < LPT; ++i) {
-            const int c = (tid + i * 256) % NC;
-            kreg[i].u = make_uint4(0, 0, 0, 0);
-            vreg[i].u = make_uint4(0, 0, 0, 0);
-            if (rows_next[i] >= 0) {
-                const size_t at = (size_t)rows_next[i] * a.C + hoff + c * 8;
-                kreg[i].u = *reinterpret_cast<const uint4*>(a.k + at);
-                vreg[i].u = *reinterpret_cast<const uint4*>(a.v + at);
-            }
+            const uint64_t at = (uint64_t)rows_next[i] * row_bytes;   // one 32x32->64 multiply-add per address
+            kreg[i] = *reinterpret_cast<const u32x4*>(kthr[i] + at);
+            vreg[i] = *reinterpret_cast<const u32x4*>(vthr[i] + at);
         }
     };
-    auto store_stage = [&](int buf) {
+    auto store_stage = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < LPT; ++i) {
+            // The loaded V words are made opaque up to here: otherwise the compiler splits them into halves
+            // right behind the load instruction, and every stage begins by waiting out the load it just issued.
+            uint32_t v0 = vreg[i].x, v1 = vreg[i].y, v2 = vreg[i].z, v3 = vreg[i].w;
+            asm volatile("" : "+v"(v0), "+v"(v1), "+v"(v2), "+v"(v3));
             const int uidx = tid + i * 256;
             const int kk = uidx / NC, c = uidx % NC;
             const int cs = c ^ ((kk >> SWZ_SHIFT) & (NC - 1));
-            *reinterpret_cast<uint4*>(&sK[buf][kk * D + cs * 8]) = kreg[i].u;
+            *reinterpret_cast<u32x4*>(&sK[buf][kk * D + cs * 8]) = kreg[i];
             // V is stored transposed, keys of a 16-block reordered to the order the MFMA result holds them
             const int w16 = kk & 15;
             const int pos = (kk & ~15) + 8 * ((w16 >> 2) & 1) + 4 * (w16 >> 3) + (w16 & 3);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) sV[buf][(c * 8 + e) * VSTR + pos] = vreg[i].h[e];
+            uint16_t* col = &sV[buf][c * 8 * VSTR + pos];
+            col[0 * VSTR] = (uint16_t)(v0 & 0xFFFFu);
+            col[1 * VSTR] = (uint16_t)(v0 >> 16);
+            col[2 * VSTR] = (uint16_t)(v1 & 0xFFFFu);
+            col[3 * VSTR] = (uint16_t)(v1 >> 16);
+            col[4 * VSTR] = (uint16_t)(v2 & 0xFFFFu);
+            col[5 * VSTR] = (uint16_t)(v2 >> 16);
+            col[6 * VSTR] = (uint16_t)(v3 & 0xFFFFu);
+            col[7 * VSTR] = (uint16_t)(v3 >> 16);
         }
     };
 
@@ -266,14 +310,14 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
         }
         fetch_rows(0);
         load_stage();
-        fetch_rows(1);
+        if (nst > 1) fetch_rows(1);
         store_stage(0);
         __syncthreads();
         for (int st = 0; st < nst; ++st) {
             const int buf = st & 1;
             if (st + 1 < nst) {
                 load_stage();            // rows of stage st+1, fetched a stage ago
-                fetch_rows(st + 2);
+                if (st + 2 < nst) fetch_rows(st + 2);
             }
             const uint16_t* kbuf = sK[buf];
             const uint16_t* vbuf = sV[buf] + voff;
