@@ -51,6 +51,13 @@ extern "C" {
 #define F3D_SHIFT 1
 #define F3D_STRIDE 2
 
+/* How the bucketing steps are put on the GPU. The result does not depend on it. AUTO picks STEPS when the
+ * per-scan count matrix is small (the paper's operating range), else GENERAL. Asking for STEPS on an input
+ * that does not qualify is F3D_ERR_UNSUPPORTED. */
+#define F3D_SCHEDULE_AUTO 0
+#define F3D_SCHEDULE_GENERAL 1 /* two launches per step, any size                                      */
+#define F3D_SCHEDULE_STEPS 2   /* one launch per step                                                  */
+
 #define F3D_MAX_PROBES 6          /* probe offsets of Algorithm 2: the six axis neighbours           */
 #define F3D_MAX_SCAN_BUCKETS 8192 /* most hash buckets one scan may own                               */
 #define F3D_MAX_SCOPE_BUCKETS 16  /* most buckets per attention scope                                 */
@@ -68,6 +75,8 @@ typedef struct f3d_params {
     int32_t probe_step;      /* probe distance in voxels; 0 = automatic                                      */
     int64_t max_scan_points; /* upper bound on the points of any one scan; 0 = n. Sizes the workspace and    */
                              /* must satisfy ceil(max_scan_points / S) <= F3D_MAX_SCAN_BUCKETS               */
+    int32_t schedule;        /* F3D_SCHEDULE_*; 0 = automatic                                                */
+    int32_t reserved;        /* 0                                                                            */
 } f3d_params;
 
 /* Fill *p with the defaults: scope_buckets 4, Z-order-div hash, 6 probes, automatic divisor and step. */

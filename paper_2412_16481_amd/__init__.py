@@ -18,6 +18,7 @@ F3D_OK = 0
 ERR_INVALID_ARG, ERR_BAD_ALIGNMENT, ERR_WORKSPACE_TOO_SMALL, ERR_UNSUPPORTED, ERR_HIP = -1, -2, -3, -4, -5
 HASHES = {"xor_mod": 0, "xor_div": 1, "zorder_mod": 2, "zorder_div": 3}
 MODES = {"plain": 0, "shift": 1, "stride": 2}
+SCHEDULES = {"auto": 0, "general": 1, "steps": 2}
 
 EXPORTS = ("f3d_params_default", "f3d_max_buckets", "f3d_workspace_bytes", "f3d_psh_bucketize",
            "f3d_bucket_swin_attn", "f3d_unpermute", "f3d_error_string", "f3d_last_hip_error", "f3d_version")
@@ -26,7 +27,8 @@ EXPORTS = ("f3d_params_default", "f3d_max_buckets", "f3d_workspace_bytes", "f3d_
 class f3d_params(ctypes.Structure):
     _fields_ = [("struct_size", ctypes.c_uint32), ("voxel_size", ctypes.c_float), ("bucket_cap", ctypes.c_int32),
                 ("scope_buckets", ctypes.c_int32), ("hash", ctypes.c_int32), ("n_probes", ctypes.c_int32),
-                ("div", ctypes.c_int32), ("probe_step", ctypes.c_int32), ("max_scan_points", ctypes.c_int64)]
+                ("div", ctypes.c_int32), ("probe_step", ctypes.c_int32), ("max_scan_points", ctypes.c_int64),
+                ("schedule", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class Flash3DError(RuntimeError):
@@ -82,7 +84,8 @@ def version() -> int:
 
 
 def make_params(voxel_size: float, bucket_cap: int, scope_buckets: int = 4, hash: str = "zorder_div",
-                n_probes: int = 6, div: int = 0, probe_step: int = 0, max_scan_points: int = 0) -> f3d_params:
+                n_probes: int = 6, div: int = 0, probe_step: int = 0, max_scan_points: int = 0,
+                schedule: str = "auto") -> f3d_params:
     p = f3d_params()
     lib().f3d_params_default(ctypes.byref(p), voxel_size, bucket_cap)
     p.scope_buckets = scope_buckets
@@ -91,6 +94,7 @@ def make_params(voxel_size: float, bucket_cap: int, scope_buckets: int = 4, hash
     p.div = div
     p.probe_step = probe_step
     p.max_scan_points = max_scan_points
+    p.schedule = SCHEDULES[schedule] if isinstance(schedule, str) else int(schedule)
     return p
 
 

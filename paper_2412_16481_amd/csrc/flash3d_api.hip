@@ -41,6 +41,7 @@ int check_params(int64_t n, int32_t n_scans, const f3d_params* p)
     if (p->hash < 0 || p->hash > 3) return F3D_ERR_INVALID_ARG;
     if (p->n_probes < 0 || p->n_probes > F3D_MAX_PROBES) return F3D_ERR_INVALID_ARG;
     if (p->div < 0 || p->probe_step < 0 || p->max_scan_points < 0) return F3D_ERR_INVALID_ARG;
+    if (p->schedule < F3D_SCHEDULE_AUTO || p->schedule > F3D_SCHEDULE_STEPS || p->reserved != 0) return F3D_ERR_INVALID_ARG;
     if (p->bucket_cap % (16 * p->scope_buckets) != 0) return F3D_ERR_INVALID_ARG;
     if (p->scope_buckets > F3D_MAX_SCOPE_BUCKETS) return F3D_ERR_UNSUPPORTED;
     if (n >= (int64_t)2147483647 - (1 << 20)) return F3D_ERR_UNSUPPORTED;
@@ -195,8 +196,12 @@ int f3d_psh_bucketize(const float* coords, const int32_t* batch_offsets, int64_t
     a.done = (int32_t*)(ws + pl.o_done);
     a.chunk_info = (int4*)(ws + pl.o_ci);
     (void)hipGetLastError();  // a stale error left by an earlier, unrelated runtime call is not ours
-    const hipError_t e = f3d::psh_fast_eligible(pl.max_scan_points, pl.kcap) ? f3d::psh_fast_launch(a, (hipStream_t)stream)
-                                                                             : f3d::psh_launch(a, (hipStream_t)stream);
+    const bool fast_ok = f3d::psh_fast_eligible(pl.max_scan_points, pl.kcap);
+    int schedule = p->schedule;
+    if (schedule == F3D_SCHEDULE_AUTO) schedule = fast_ok ? F3D_SCHEDULE_STEPS : F3D_SCHEDULE_GENERAL;
+    if (schedule == F3D_SCHEDULE_STEPS && !fast_ok) return F3D_ERR_UNSUPPORTED;
+    const hipError_t e = schedule == F3D_SCHEDULE_GENERAL ? f3d::psh_launch(a, (hipStream_t)stream)
+                                                          : f3d::psh_fast_launch(a, (hipStream_t)stream);
     return e == hipSuccess ? F3D_OK : hip_fail(e);
 }
 

@@ -19,12 +19,6 @@ namespace f3d {
 
 namespace {
 
-#ifdef F3D_PSH_TIMING  // development aid: phase time stamps of workgroup 0 into the (otherwise unused) freepre array
-#define TSTAMP(row, slot) do { if (threadIdx.x == 0 && blockIdx.x == 0) reinterpret_cast<long long*>(a.freepre)[(row) * 16 + (slot)] = (long long)wall_clock64(); } while (0)
-#else
-#define TSTAMP(row, slot) do { } while (0)
-#endif
-
 constexpr int FCH = 2048;    // points per workgroup
 constexpr int FTH = 512;     // threads per workgroup
 constexpr int FW = FTH / 64; // waves
@@ -102,7 +96,6 @@ __global__ __launch_bounds__(FTH) void k_pshf_step(PshArgs a, int r, const uint3
     extern __shared__ int smem[];
     __shared__ ScanCfg cfg;
     __shared__ int placed_ct;
-    TSTAMP(r, 0);
     const int chunk = blockIdx.x;
     const ChunkInfo ci = load_chunk(a, chunk);
     if (ci.b < 0 || a.status[0]) return;
@@ -113,7 +106,6 @@ __global__ __launch_bounds__(FTH) void k_pshf_step(PshArgs a, int r, const uint3
     int* pre = smem + a.kcap;                       // [kcap] ... of earlier chunks; then rebased fill level
     uint32_t* wh = (uint32_t*)(smem + 2 * a.kcap);  // [FW][kwp]
     const bool last_step = (r == a.n_probes + 1);
-    TSTAMP(r, 1);
 
     // ---- every global load of this kernel is issued here, before anything waits
     uint32_t box[8];
@@ -175,7 +167,6 @@ __global__ __launch_bounds__(FTH) void k_pshf_step(PshArgs a, int r, const uint3
 #pragma unroll
         for (int j = 0; j < KPT; ++j) cntv[j] = (tid + j * FTH < K) ? a.cnt[kb0 + tid + j * FTH] : 0;
     }
-    TSTAMP(r, 2);
 
     // ---- LDS set-up while the loads fly
     for (int w = tid; w < FW * kwp; w += FTH) wh[w] = 0u;
@@ -191,7 +182,6 @@ __global__ __launch_bounds__(FTH) void k_pshf_step(PshArgs a, int r, const uint3
         reinterpret_cast<uint32_t*>(&cfg)[tid] = cfgw;
     }
     __syncthreads();
-    TSTAMP(r, 3);
     if (r > 0) {
         if (seg < nseg) {
 #pragma unroll
@@ -217,7 +207,6 @@ __global__ __launch_bounds__(FTH) void k_pshf_step(PshArgs a, int r, const uint3
         }
         __syncthreads();
     }
-    TSTAMP(r, 4);
 
     const int keybits = last_step ? 0 : max(1, 32 - __clz(max(K - 1, 1)));
     int hh[FPPT], wl[FPPT];
@@ -257,7 +246,6 @@ __global__ __launch_bounds__(FTH) void k_pshf_step(PshArgs a, int r, const uint3
         act[s] = active;
         hh[s] = h;
     }
-    TSTAMP(r, 5);
     // rank inside the chunk: ballots inside the wave, per-wave LDS counters across the wave's four steps
 #pragma unroll
     for (int s = 0; s < FPPT; ++s) {
@@ -278,7 +266,6 @@ __global__ __launch_bounds__(FTH) void k_pshf_step(PshArgs a, int r, const uint3
         if (!active) hh[s] = -1;
         wl[s] = old;
     }
-    TSTAMP(r, 6);
     __syncthreads();
     // join the waves: exclusive prefix over the waves per bucket; the total is this chunk's row
     if (!last_step) {
@@ -313,14 +300,12 @@ __global__ __launch_bounds__(FTH) void k_pshf_step(PshArgs a, int r, const uint3
             a.key[i] = ((uint32_t)h << LR_BITS) | (uint32_t)(base + wl[s]);
         }
     }
-    TSTAMP(r, 7);
     if (r > 0) {
         for (int d = 32; d >= 1; d >>= 1) nplaced += __shfl_xor(nplaced, d, 64);
         if (lane == 0 && nplaced) atomicAdd(&placed_ct, nplaced);
         __syncthreads();
         if (tid == 0 && placed_ct) atomicAdd(&a.round_count[r - 1], placed_ct);
     }
-    TSTAMP(r, 8);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -331,7 +316,6 @@ __global__ __launch_bounds__(FTH) void k_pshf_recycle(PshArgs a)
     extern __shared__ int smem[];
     __shared__ int lds[17];
     __shared__ int s_base;
-    TSTAMP(10, 0);
     const int chunk = blockIdx.x;
     const ChunkInfo ci = load_chunk(a, chunk);
     if (ci.b < 0 || a.status[0]) return;
@@ -355,7 +339,6 @@ __global__ __launch_bounds__(FTH) void k_pshf_recycle(PshArgs a)
     const int p0 = ci.begin - lc * FCH;
     const int nb = a.scan_p0[ci.b + 1] - p0;
     if (my_left == 0) return;   // uniform: nothing of this chunk is left over
-    TSTAMP(10, 1);
     // leftovers of earlier chunks
     int tot;
     block_excl_scan(mine, &tot, lds);
@@ -378,7 +361,6 @@ __global__ __launch_bounds__(FTH) void k_pshf_recycle(PshArgs a)
         }
     }
     __syncthreads();
-    TSTAMP(10, 2);
     const int base = s_base;
     int placed = 0;
 #pragma unroll
@@ -399,7 +381,6 @@ __global__ __launch_bounds__(FTH) void k_pshf_recycle(PshArgs a)
     }
     for (int d = 32; d >= 1; d >>= 1) placed += __shfl_xor(placed, d, 64);
     if ((tid & 63) == 0 && placed) atomicAdd(&a.round_count[a.n_probes + 1], placed);
-    TSTAMP(10, 3);
 }
 
 }  // namespace

@@ -27,8 +27,9 @@ def dev(a, dtype=None):
     return t.to(DEV)
 
 
-def run_bucketize(coords, bo, voxel, cap, m=4, hash="zorder_div", n_probes=6, max_scan_points=0, div=0, probe_step=0):
-    p = f3d.make_params(voxel, cap, m, hash, n_probes, div, probe_step, max_scan_points)
+def run_bucketize(coords, bo, voxel, cap, m=4, hash="zorder_div", n_probes=6, max_scan_points=0, div=0, probe_step=0,
+                  schedule="auto"):
+    p = f3d.make_params(voxel, cap, m, hash, n_probes, div, probe_step, max_scan_points, schedule)
     bk = f3d.psh_bucketize(dev(coords), None if bo is None else dev(bo.astype(np.int32)), p)
     torch.cuda.synchronize()
     return bk
@@ -58,6 +59,34 @@ def check_bucketize(coords, bo, voxel, cap, m=4, hash="zorder_div", n_probes=6, 
 def test_bucketize_matches_oracle_on_workloads(name, hash):
     w = wl.make_workload(name)
     check_bucketize(w.coords, w.batch_offsets, w.voxel_size, w.bucket_cap, w.scope_buckets, hash)
+
+
+@pytest.mark.parametrize("schedule", ["general", "steps"])
+@pytest.mark.parametrize("name,hash", [("tiny", "xor_mod"), ("indoor", "zorder_div"), ("indoor", "xor_div"), ("lidar4", "zorder_mod")])
+def test_bucketize_every_schedule_gives_the_oracle_result(name, hash, schedule):
+    # the two ways of putting the steps on the GPU (two launches per step, one per step) are the same function
+    w = wl.make_workload(name)
+    largest = int(np.diff(w.batch_offsets).max()) if w.batch_offsets is not None else w.n   # sizes the count matrix per scan
+    check_bucketize(w.coords, w.batch_offsets, w.voxel_size, w.bucket_cap, w.scope_buckets, hash, schedule=schedule,
+                    max_scan_points=largest)
+
+
+@pytest.mark.parametrize("schedule", ["general", "steps"])
+def test_bucketize_schedules_on_ragged_scans(schedule):
+    rng = np.random.default_rng(27)
+    sizes = [1, 2047, 2048, 2049, 0, 5000, 77, 0, 12000]
+    bo = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    c = np.concatenate([wl.uniform_cube(rng, s, 1.0 + i) + 10.0 * i for i, s in enumerate(sizes)]).astype(np.float32)
+    for n_probes in (0, 3, 6):
+        check_bucketize(c, bo, 0.05, 256, 4, "zorder_div", n_probes, schedule=schedule)
+
+
+def test_bucketize_one_launch_per_step_is_refused_for_a_large_count_matrix():
+    w = wl.make_workload("lidar8")   # taken as ONE scan of 9e5 points: 447 chunks x 3573 buckets
+    p = f3d.make_params(w.voxel_size, w.bucket_cap, w.scope_buckets, "zorder_div", schedule="steps")
+    with pytest.raises(f3d.Flash3DError) as e:
+        f3d.psh_bucketize(dev(w.coords), None, p)
+    assert e.value.code == f3d.ERR_UNSUPPORTED
 
 
 @pytest.mark.parametrize("n", [1, 5, 63, 64, 65, 1023, 1024, 1025, 4097, 20000])
