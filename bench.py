@@ -2,8 +2,9 @@
 """Benchmark of the hot path on one MI355X: PSH bucketize -> Bucket-Swin attention passes -> unpermute.
 
 One "step" is one pass of the whole path over one batch of seeded synthetic points: one
-f3d_psh_bucketize, one f3d_bucket_swin_attn per pass of the workload, one f3d_unpermute. Inputs are
-resident in HBM before the timed region. Prints ONE JSON line:
+f3d_psh_bucketize, one f3d_bucket_swin_attn per pass of the workload, and the unpermute, which the last
+pass does in its own store (out_perm); --separate-unpermute runs it as f3d_unpermute instead. Either way the
+step ends with the result in the input order of the points. Inputs are resident in HBM before the timed region. Prints ONE JSON line:
   value     = points / second over the whole step (whole job, one GPU)
   roofline  = the attention kernel (dominant): algorithmic FLOP (sum over scopes of 4*n_g^2*C) divided by
               its mean launch duration from HIP events on the launch stream, against 2.5 PFLOP/s bf16 MFMA
@@ -84,6 +85,8 @@ def main() -> int:
     ap.add_argument("--hash", default="zorder_div")
     ap.add_argument("--cpu-rows", type=int, default=-1,
                     help="query rows the oracle computes per pass (-1 = about 20 s of host work, 0 = skip)")
+    ap.add_argument("--separate-unpermute", dest="fuse_unpermute", action="store_false",
+                    help="run f3d_unpermute as a kernel of its own instead of folding it into the last pass's store")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="also run one plain device copy of this many MiB (counter calibration for rocprofv3 --pmc runs)")
     args = ap.parse_args()
@@ -123,20 +126,27 @@ def main() -> int:
         sz = scope_sizes(offsets, sbs, m, mode, 2, 2)
         flops[mode] = float((4.0 * sz.astype(np.float64) ** 2 * C).sum())
 
-    def step(events=None):
-        def mark():
-            if events is not None:
+    def step(events=None, detail=False):
+        """One pass of the whole path. In the timed region only the group of attention launches is bracketed by
+        events (an event costs a few microseconds of stream time); detail=True marks every part."""
+        def mark(always=False):
+            if events is not None and (detail or always):
                 e = torch.cuda.Event(enable_timing=True)
                 e.record()
                 events.append(e)
         mark()
         f3d.psh_bucketize(coords, bo, p, ws, bk)
-        mark()
-        for mode in w.modes:
-            f3d.bucket_swin_attn(q, k, v, bk, H, d, mode, 2, 2, not bucket_major, 0.0, out)
+        mark(True)
+        for i, mode in enumerate(w.modes):
+            last = i + 1 == len(w.modes)
+            if not last or not args.fuse_unpermute:
+                f3d.bucket_swin_attn(q, k, v, bk, H, d, mode, 2, 2, not bucket_major, 0.0, out)
+            else:   # the last pass stores its rows straight at their input positions
+                f3d.bucket_swin_attn(q, k, v, bk, H, d, mode, 2, 2, not bucket_major, 0.0, back, True)
+            mark(last)
+        if not args.fuse_unpermute:
+            f3d.unpermute(out, bk.perm, back)
             mark()
-        f3d.unpermute(out, bk.perm, back)
-        mark()
 
     for _ in range(args.warmup):
         step()
@@ -156,13 +166,20 @@ def main() -> int:
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
 
-    # per-part durations from the events recorded on the launch stream inside the timed region
-    parts = np.array([[ev[i].elapsed_time(ev[i + 1]) for i in range(len(ev) - 1)] for ev in all_events])  # ms
+    # the attention kernel: mean launch duration from the events recorded on the launch stream inside the timed region
+    attn_ms_per_launch = float(np.mean([ev[0].elapsed_time(ev[1]) for ev in all_events])) / len(w.modes)
+    # every part by itself, from a short loop after the timed region (events around each launch)
+    detail = []
+    for _ in range(min(args.steps, 10)):
+        ev = []
+        step(ev, True)
+        detail.append(ev)
+    torch.cuda.synchronize()
+    parts = np.array([[ev[i].elapsed_time(ev[i + 1]) for i in range(len(ev) - 1)] for ev in detail])  # ms
     t_buck = parts[:, 0].mean()
     t_attn = parts[:, 1:1 + len(w.modes)]
-    t_unp = parts[:, -1].mean()
+    t_unp = parts[:, -1].mean() if not args.fuse_unpermute else 0.0
     attn_flop_per_launch = np.mean([flops[mo] for mo in w.modes])
-    attn_ms_per_launch = t_attn.mean()
     tflops = attn_flop_per_launch / (attn_ms_per_launch * 1e-3) / 1e12
     buck_gbps = 20.0 * n / (t_buck * 1e-3) / 1e9
 
@@ -181,11 +198,13 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "points": n, "scans": w.n_scans, "channels": C, "heads": H, "head_dim": d,
                    "bucket_cap": w.bucket_cap, "scope_buckets": m, "hash": args.hash, "passes": w.modes,
-                   "features": "bucket-major" if bucket_major else "input order, gathered through perm"},
+                   "features": "bucket-major" if bucket_major else "input order, gathered through perm",
+                   "unpermute": "in the last pass's store" if args.fuse_unpermute else "separate kernel"},
         "roofline": {"bound": "mfma", "kernel": "k_attn", "achieved": tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": tflops / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
                      "flop_per_launch": attn_flop_per_launch, "ms_per_launch": attn_ms_per_launch},
-        "parts_ms": {"bucketize": t_buck, "attn_per_pass": [float(x) for x in t_attn.mean(axis=0)], "unpermute": t_unp},
+        "parts_ms": {"bucketize": float(t_buck), "attn_per_pass": [float(x) for x in t_attn.mean(axis=0)], "unpermute": float(t_unp),
+                     "from": "events around every launch, in a short loop after the timed region"},
         "bucketize": {"bound": "hbm", "achieved": buck_gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                       "frac": buck_gbps / PEAK_HBM_GBPS, "bytes_per_point": 20,
                       "placed_share": {"direct": float(placed[0]) / n, "probes": float(placed[1:7].sum()) / n,

@@ -423,12 +423,15 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
         if (__syncthreads_or(bad)) sweep(std::true_type{});
     }
 
-    // ---- epilogue: divide by the softmax denominator, round to bf16, store at the query's own row
+    // ---- epilogue: divide by the softmax denominator, round to bf16, store
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
         if (orow[t] >= 0) {
             const float inv = 1.0f / den[t];
-            uint16_t* dst = a.out + (size_t)orow[t] * a.C + hoff;   // bucket-major row, never through perm
+            // the query's own bucket-major row, or straight to where the caller wants that row (the inverse of the
+            // up-front scatter folded into the last layer's store: same 32-byte pieces, no extra pass)
+            const size_t drow = a.out_perm ? (size_t)a.out_perm[orow[t]] : (size_t)orow[t];
+            uint16_t* dst = a.out + drow * a.C + hoff;
             constexpr int NB = D / 8;
 #pragma unroll
             for (int blk = 0; blk < NB; ++blk) {

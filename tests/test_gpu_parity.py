@@ -321,3 +321,19 @@ def test_end_to_end_original_order():
     want = oracle.unpermute(oracle.attn(q, k, v, ref["perm"], ref["offsets"], ref["scan_bucket_start"], 4, "shift",
                                         w.heads, w.head_dim), ref["perm"])
     assert np.abs(back.float().cpu().numpy() - want).max() <= ATOL
+
+
+@pytest.mark.parametrize("name,bucket_major", [("tiny", False), ("indoor", False), ("lidar8", True)])
+def test_attention_stores_in_input_order_on_request(name, bucket_major):
+    # the unpermute folded into the attention kernel's store is the same function as the separate kernel: bit for bit
+    w = wl.make_workload(name)
+    largest = int(np.diff(w.batch_offsets).max())
+    bk = run_bucketize(w.coords, w.batch_offsets, w.voxel_size, w.bucket_cap, w.scope_buckets, max_scan_points=largest)
+    q, k, v = (dev(x, torch.bfloat16) for x in w.qkv())
+    if bucket_major:
+        q, k, v = (x[bk.perm.long()].contiguous() for x in (q, k, v))
+    for mode in dict.fromkeys(w.modes):
+        two_step = f3d.unpermute(f3d.bucket_swin_attn(q, k, v, bk, w.heads, w.head_dim, mode, 2, 2, not bucket_major), bk.perm)
+        fused = f3d.bucket_swin_attn(q, k, v, bk, w.heads, w.head_dim, mode, 2, 2, not bucket_major, original_order=True)
+        torch.cuda.synchronize()
+        assert torch.equal(fused, two_step)
