@@ -89,10 +89,14 @@ __global__ __launch_bounds__(FTH) void k_pshf_minmax(PshArgs a)
 
 // ------------------------------------------------------------------------------------------------
 // step r: settle step r-1 from the count rows of that step, then rank the contenders of step r
-// dynamic LDS: tot[kcap] + pre[kcap] ints + FW x kwp words of packed 16-bit counters
-__global__ __launch_bounds__(FTH) void k_pshf_step(PshArgs a, int r, const uint32_t* __restrict__ mat_prev,
+// dynamic LDS: tot[kcap] + pre[kcap] ints + NW x kwp words of packed 16-bit counters.
+// TH threads rank the 2048 points of a chunk: 512 (four points each, two workgroups per CU) when the grid is
+// larger than the GPU, 1024 (two points each: every phase of the step is half as long) when it is not.
+template <int TH>
+__global__ __launch_bounds__(TH) void k_pshf_step(PshArgs a, int r, const uint32_t* __restrict__ mat_prev,
                                                    uint32_t* __restrict__ mat_cur)
 {
+    constexpr int NW = TH / 64, PPT = FCH / TH, KPT_ = FKMAX / TH;
     extern __shared__ int smem[];
     __shared__ ScanCfg cfg;
     __shared__ int placed_ct;
@@ -104,7 +108,7 @@ __global__ __launch_bounds__(FTH) void k_pshf_step(PshArgs a, int r, const uint3
     const int kwp = row_pitch(a.kcap);
     int* tot = smem;                                // [kcap] contenders of step r-1 per bucket, all chunks
     int* pre = smem + a.kcap;                       // [kcap] ... of earlier chunks; then rebased fill level
-    uint32_t* wh = (uint32_t*)(smem + 2 * a.kcap);  // [FW][kwp]
+    uint32_t* wh = (uint32_t*)(smem + 2 * a.kcap);  // [NW][kwp]
     const bool last_step = (r == a.n_probes + 1);
 
     // ---- every global load of this kernel is issued here, before anything waits
@@ -116,11 +120,11 @@ __global__ __launch_bounds__(FTH) void k_pshf_step(PshArgs a, int r, const uint3
     } else if (tid < CFGW) {
         cfgw = reinterpret_cast<const uint32_t*>(reinterpret_cast<const ScanCfg*>(a.cfg) + ci.b)[tid];
     }
-    uint32_t kwv[FPPT];
-    float cx[FPPT], cy[FPPT], cz[FPPT];
+    uint32_t kwv[PPT];
+    float cx[PPT], cy[PPT], cz[PPT];
 #pragma unroll
-    for (int s = 0; s < FPPT; ++s) {
-        const int i = ci.begin + wave * (FCH / FW) + s * 64 + lane;
+    for (int s = 0; s < PPT; ++s) {
+        const int i = ci.begin + wave * (FCH / NW) + s * 64 + lane;
         kwv[s] = KEY_PLACED;
         cx[s] = cy[s] = cz[s] = 0.f;
         if (i < ci.end) {
@@ -134,8 +138,8 @@ __global__ __launch_bounds__(FTH) void k_pshf_step(PshArgs a, int r, const uint3
     // Count rows of step r-1, 16 bytes (8 buckets) per load: thread (g, seg) sums column group g over
     // rows seg, seg+nseg, ... in registers; the row segments are joined in LDS afterwards.
     const int G = (((K + 1) >> 1) + 3) >> 2;        // column groups in use (<= 256)
-    const int nseg = FTH / G, seg = tid / G, g = tid - seg * G;
-    int tl[8], pl[8], cntv[KPT];
+    const int nseg = TH / G, seg = tid / G, g = tid - seg * G;
+    int tl[8], pl[8], cntv[KPT_];
 #pragma unroll
     for (int e = 0; e < 8; ++e) { tl[e] = 0; pl[e] = 0; }
     if (r > 0) {
@@ -165,13 +169,13 @@ __global__ __launch_bounds__(FTH) void k_pshf_step(PshArgs a, int r, const uint3
             }
         }
 #pragma unroll
-        for (int j = 0; j < KPT; ++j) cntv[j] = (tid + j * FTH < K) ? a.cnt[kb0 + tid + j * FTH] : 0;
+        for (int j = 0; j < KPT_; ++j) cntv[j] = (tid + j * TH < K) ? a.cnt[kb0 + tid + j * TH] : 0;
     }
 
     // ---- LDS set-up while the loads fly
-    for (int w = tid; w < FW * kwp; w += FTH) wh[w] = 0u;
+    for (int w = tid; w < NW * kwp; w += TH) wh[w] = 0u;
     if (r > 0)
-        for (int k = tid; k < 2 * a.kcap; k += FTH) smem[k] = 0;
+        for (int k = tid; k < 2 * a.kcap; k += TH) smem[k] = 0;
     if (tid == 0) placed_ct = 0;
     if (r == 0) {
         if (tid == 0) {
@@ -197,8 +201,8 @@ __global__ __launch_bounds__(FTH) void k_pshf_step(PshArgs a, int r, const uint3
         // fill level before step r-1 plus earlier chunks' contenders = first rank of this chunk's contenders;
         // chunk 0 of the scan also publishes the fill level after step r-1
 #pragma unroll
-        for (int j = 0; j < KPT; ++j) {
-            const int k = tid + j * FTH;
+        for (int j = 0; j < KPT_; ++j) {
+            const int k = tid + j * TH;
             if (k < K) {
                 const int base = cntv[j];
                 if (lc == 0) a.cnt_next[kb0 + k] = min(base + tot[k], k == K - 1 ? cfg.lastcap : a.S);
@@ -209,13 +213,13 @@ __global__ __launch_bounds__(FTH) void k_pshf_step(PshArgs a, int r, const uint3
     }
 
     const int keybits = last_step ? 0 : max(1, 32 - __clz(max(K - 1, 1)));
-    int hh[FPPT], wl[FPPT];
-    bool act[FPPT];
+    int hh[PPT], wl[PPT];
+    bool act[PPT];
     int nplaced = 0;
     // accept what fits from step r-1, hash what is left for step r
 #pragma unroll
-    for (int s = 0; s < FPPT; ++s) {
-        const int i = ci.begin + wave * (FCH / FW) + s * 64 + lane;
+    for (int s = 0; s < PPT; ++s) {
+        const int i = ci.begin + wave * (FCH / NW) + s * 64 + lane;
         bool active = i < ci.end;
         int h = 0;
         if (active && r > 0) {
@@ -248,7 +252,7 @@ __global__ __launch_bounds__(FTH) void k_pshf_step(PshArgs a, int r, const uint3
     }
     // rank inside the chunk: ballots inside the wave, per-wave LDS counters across the wave's four steps
 #pragma unroll
-    for (int s = 0; s < FPPT; ++s) {
+    for (int s = 0; s < PPT; ++s) {
         const int h = hh[s];
         const bool active = act[s];
         const unsigned long long m = match_key(h, active, keybits);
@@ -269,11 +273,11 @@ __global__ __launch_bounds__(FTH) void k_pshf_step(PshArgs a, int r, const uint3
     __syncthreads();
     // join the waves: exclusive prefix over the waves per bucket; the total is this chunk's row
     if (!last_step) {
-        for (int w = tid; w < kwp; w += FTH) {
+        for (int w = tid; w < kwp; w += TH) {
             uint32_t run = 0;
             if (2 * w < K) {
 #pragma unroll
-                for (int v = 0; v < FW; ++v) {
+                for (int v = 0; v < NW; ++v) {
                     const uint32_t t = wh[v * kwp + w];
                     wh[v * kwp + w] = run;
                     run += t;  // halves cannot carry into each other: a chunk has 2048 points
@@ -283,7 +287,7 @@ __global__ __launch_bounds__(FTH) void k_pshf_step(PshArgs a, int r, const uint3
         }
     } else if (tid == 0) {
         uint32_t run = 0;
-        for (int v = 0; v < FW; ++v) {
+        for (int v = 0; v < NW; ++v) {
             const uint32_t t = wh[v * kwp];
             wh[v * kwp] = run;
             run += t;
@@ -292,8 +296,8 @@ __global__ __launch_bounds__(FTH) void k_pshf_step(PshArgs a, int r, const uint3
     }
     __syncthreads();
 #pragma unroll
-    for (int s = 0; s < FPPT; ++s) {
-        const int i = ci.begin + wave * (FCH / FW) + s * 64 + lane;
+    for (int s = 0; s < PPT; ++s) {
+        const int i = ci.begin + wave * (FCH / NW) + s * 64 + lane;
         if (hh[s] >= 0) {
             const int h = hh[s];
             const int base = (int)((wh[wave * kwp + (h >> 1)] >> ((h & 1) * 16)) & 0xFFFFu);
@@ -406,9 +410,14 @@ hipError_t psh_fast_launch(const PshArgs& args, hipStream_t stream)
     if (a.n == 0) return hipGetLastError();
     k_pshf_minmax<<<chunks, FTH, 0, stream>>>(a);
     const int kwp = row_pitch(a.kcap);
-    const size_t lds = (size_t)a.kcap * 8 + (size_t)FW * kwp * 4;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
+    const bool wide = chunks <= cus;   // one workgroup per CU at most: take the 1024-thread form
+    const int nw = wide ? 16 : 8;
+    const size_t lds = (size_t)a.kcap * 8 + (size_t)nw * kwp * 4;
     if (lds > 60000) {
-        const hipError_t e = hipFuncSetAttribute((const void*)k_pshf_step, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        const hipError_t e = wide ? hipFuncSetAttribute((const void*)k_pshf_step<1024>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
+                                  : hipFuncSetAttribute((const void*)k_pshf_step<512>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
     uint32_t* mat[2] = {reinterpret_cast<uint32_t*>(a.hist), reinterpret_cast<uint32_t*>(a.hist) + (size_t)chunks * kwp};
@@ -417,7 +426,8 @@ hipError_t psh_fast_launch(const PshArgs& args, hipStream_t stream)
     for (int r = 0; r <= a.n_probes + 1; ++r) {
         a.cnt = c0;
         a.cnt_next = c1;
-        k_pshf_step<<<chunks, FTH, lds, stream>>>(a, r, mat[(r + 1) & 1], mat[r & 1]);
+        if (wide) k_pshf_step<1024><<<chunks, 1024, lds, stream>>>(a, r, mat[(r + 1) & 1], mat[r & 1]);
+        else k_pshf_step<512><<<chunks, 512, lds, stream>>>(a, r, mat[(r + 1) & 1], mat[r & 1]);
         if (r > 0) { int32_t* t = c0; c0 = c1; c1 = t; }  // step r wrote the fill levels after step r-1
     }
     a.cnt = c0;

@@ -97,6 +97,14 @@ def test_bucketize_small_and_ragged_sizes(n):
         check_bucketize(c, None, 0.05, 64, 4, hash)
 
 
+def test_bucketize_widest_count_rows_on_the_one_launch_per_step_path():
+    # 2048 buckets in one scan of 64 chunks: the largest LDS footprint of the step kernel (above the 64 KB default)
+    rng = np.random.default_rng(28)
+    c = wl.uniform_cube(rng, 2048 * 64, 3.0)
+    check_bucketize(c, None, 0.02, 256, 4, "zorder_mod", schedule="steps")
+    check_bucketize(c[:2048 * 64 - 100], None, 0.02, 256, 4, "xor_div", n_probes=2, schedule="steps")
+
+
 def test_bucketize_empty_input_and_empty_scans():
     c = np.zeros((0, 3), dtype=np.float32)
     bk = run_bucketize(c, np.array([0, 0, 0]), 0.05, 64)
