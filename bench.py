@@ -28,7 +28,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 
 # HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/), keyed by workload.
-MEASURED_TRAFFIC_BYTES = {"indoor": 105.7e6}
+MEASURED_TRAFFIC_BYTES = {"indoor": 105.8e6, "lidar8": 1874.0e6}
 
 
 def scope_sizes(offsets: np.ndarray, sbs: np.ndarray, m: int, mode: str, shift: int, stride: int) -> np.ndarray:
