@@ -76,6 +76,36 @@ def cpu_baseline(w, sample_rows: int):
             "seconds": round(t_b + t_rows, 3)}
 
 
+def measured_ceilings(head_dim: int) -> dict:
+    """What this GPU sustains on the attention kernel's instruction mix with no memory traffic (register-only
+    loops, random operand bits), best over 1..8 waves per SIMD: the matrix core alone, the exponential + bf16-pack
+    work of the softmax alone, and the head_dim-16 tile loop (two score MFMAs, 16 exp, 8 packs, two P V MFMAs)."""
+    import ctypes
+
+    import torch  # noqa: F401  (the HIP runtime that is already loaded)
+    mb = ctypes.CDLL(os.path.join(ROOT, "paper_2412_16481_amd", "libf3d_microbench.so"))
+    mb.f3d_mb_run.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)]
+    best = {}
+    for kind, name in ((0, "mfma_only"), (1, "softmax_only"), (2, "tile_loop")):
+        for wps in (1, 2, 3, 4, 5, 6, 8):
+            ms, work = ctypes.c_float(0), ctypes.c_double(0)
+            rc = mb.f3d_mb_run(kind, wps, ctypes.byref(ms), ctypes.byref(work))
+            if rc != 0:
+                raise RuntimeError(f"f3d_mb_run failed: hipError {rc}")
+            rate = work.value / (ms.value * 1e-3)
+            if name not in best or rate > best[name][0]:
+                best[name] = (rate, wps)
+    flop_per_elem = 4.0 * head_dim   # QK^T and PV, per score element
+    return {
+        "mfma_only_tflops": best["mfma_only"][0] / 1e12, "mfma_only_waves_per_simd": best["mfma_only"][1],
+        "softmax_only_gelem_per_s": best["softmax_only"][0] / 1e9,
+        "softmax_only_as_attention_tflops": best["softmax_only"][0] * flop_per_elem / 1e12,
+        "tile_loop_gelem_per_s": best["tile_loop"][0] / 1e9, "tile_loop_waves_per_simd": best["tile_loop"][1],
+        "tile_loop_as_attention_tflops_d16": best["tile_loop"][0] * 64.0 / 1e12,
+        "note": "register-only loops, random operand bits, best over 1..8 waves per SIMD; elements = score elements",
+    }
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -87,6 +117,9 @@ def main() -> int:
                     help="query rows the oracle computes per pass (-1 = about 20 s of host work, 0 = skip)")
     ap.add_argument("--separate-unpermute", dest="fuse_unpermute", action="store_false",
                     help="run f3d_unpermute as a kernel of its own instead of folding it into the last pass's store")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="also run the register-only issue-rate microbenchmark (MFMA only, softmax only, the attention "
+                         "tile loop) and add its rates to the JSON line")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="also run one plain device copy of this many MiB (counter calibration for rocprofv3 --pmc runs)")
     args = ap.parse_args()
@@ -210,6 +243,8 @@ def main() -> int:
                       "placed_share": {"direct": float(placed[0]) / n, "probes": float(placed[1:7].sum()) / n,
                                        "recycle": float(placed[7]) / n}},
     }
+    if args.ceilings:
+        res["ceilings"] = measured_ceilings(d)
     cpu_rows = args.cpu_rows
     if cpu_rows < 0:   # the whole indoor workload costs about 20 s on 8 cores; keep other workloads to the same work
         cpu_rows = int(min(n, 2.6e13 / (w.bucket_cap * C * len(w.modes))))
