@@ -46,6 +46,8 @@ def lib() -> ctypes.CDLL:
         _lib.orc_attn.restype = ctypes.c_int64
         _lib.orc_unpermute.restype = ctypes.c_int
         _lib.orc_max_threads.restype = ctypes.c_int
+        _lib.orc_pool_assign.restype = ctypes.c_int64
+        _lib.orc_pool_reduce.restype = ctypes.c_int
     return _lib
 
 
@@ -127,6 +129,51 @@ def unpermute(src: np.ndarray, perm: np.ndarray) -> np.ndarray:
     rb = src.strides[0]
     lib().orc_unpermute(_p(src), _p(pm), ctypes.c_int64(src.shape[0]), ctypes.c_int64(rb), _p(dst))
     return dst
+
+
+POOL_OPS = {"sum": 0, "mean": 1, "min": 2, "max": 3}
+
+
+def pool_assign(coords_bm: np.ndarray, row_offsets: np.ndarray, tile: int, rho: int, voxel_size: float,
+                hash_name: str = "zorder_div") -> Dict[str, np.ndarray]:
+    """Sub-bucket construction of the in-bucket pooling (Appendix "In-bucket Pooling") on BUCKET-MAJOR
+    coordinates, tile by tile. Returns sub_of, slot_of, step_of (per input row), pooled_offsets
+    [n_scans+1] and n_out."""
+    c = np.ascontiguousarray(coords_bm, dtype=np.float32).reshape(-1, 3)
+    ro = np.ascontiguousarray(row_offsets, dtype=np.int32)
+    n = c.shape[0]
+    out = {k: np.full(n, -1, dtype=np.int32) for k in ("sub_of", "slot_of", "step_of")}
+    po = np.zeros(ro.shape[0], dtype=np.int32)
+    r = lib().orc_pool_assign(_p(c), _p(ro), ctypes.c_int32(ro.shape[0] - 1), ctypes.c_int32(tile), ctypes.c_int32(rho),
+                              ctypes.c_float(voxel_size), ctypes.c_int32(HASHES[hash_name]), _p(out["sub_of"]),
+                              _p(out["slot_of"]), _p(out["step_of"]), _p(po))
+    if r < 0:
+        raise ValueError("orc_pool_assign: bad arguments")
+    out["pooled_offsets"] = po
+    out["n_out"] = int(r)
+    return out
+
+
+def pool_reduce(feat_bm: np.ndarray, sub_of: np.ndarray, n_out: int, op: str = "mean",
+                coords_bm: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+    """Reduce the rows of every sub-bucket in binary64, rounded once to bf16. feat_bm: uint16 bf16 bit
+    patterns [n, C], bucket-major. Returns feat [n_out, C] (uint16), counts [n_out] and, when coords_bm is
+    given, coords [n_out, 3] (mean position, float32)."""
+    f = np.ascontiguousarray(feat_bm, dtype=np.uint16)
+    so = np.ascontiguousarray(sub_of, dtype=np.int32)
+    n, C = f.shape
+    out = np.zeros((n_out, C), dtype=np.uint16)
+    counts = np.zeros(n_out, dtype=np.int32)
+    c = None if coords_bm is None else np.ascontiguousarray(coords_bm, dtype=np.float32).reshape(-1, 3)
+    pc = None if c is None else np.zeros((n_out, 3), dtype=np.float32)
+    r = lib().orc_pool_reduce(_p(f), ctypes.c_int64(n), ctypes.c_int32(C), _p(so), ctypes.c_int64(n_out),
+                              ctypes.c_int32(POOL_OPS[op]), _p(out), _p(counts), _p(c), _p(pc))
+    if r < 0:
+        raise ValueError("orc_pool_reduce: bad arguments")
+    res = {"feat": out, "counts": counts}
+    if pc is not None:
+        res["coords"] = pc
+    return res
 
 
 def max_threads() -> int:

@@ -11,6 +11,7 @@
  *   - scatter index bucket_base[bucket_id] + bucket_off  (Section 4.1, "Input and Output")
  *   - scope regrouping: plain / shifted / strided        (Section 4.2, worked example; Table 2 caption)
  *   - multi-head self-attention inside one scope         (Section 4.2; Appendix "Bucket-Swin")
+ *   - in-bucket pooling: sub-bucket construction, reduce  (Section 4.2 "In-bucket Pooling"; Appendix "In-bucket Pooling")
  *
  * Algorithms 1 and 2 let hardware atomics decide the arrival order, so their result depends on
  * the schedule. The oracle fixes one admissible schedule: all points take the same step together
@@ -26,7 +27,9 @@
  * Parity pins (see tests/test_oracle_*.py): hand-computed hashes and Morton codes, the paper's
  * regrouping example, a literal thread-by-thread simulation of Algorithms 1+2, stable-argsort on
  * overflow-free inputs, brute-force masked dense attention, a library dense-attention routine on
- * the single-scope case, closed forms and invariants. No function here is unpinned.
+ * the single-scope case, closed forms and invariants; for the pooling hand traces of the three steps, a
+ * literal simulation with an AtomicInc primitive, capacity/coverage invariants, a brute-force
+ * nearest-sub-bucket check and numpy reductions with an independent bf16 rounding. No function here is unpinned.
  */
 #include <math.h>
 #include <stdint.h>
@@ -366,6 +369,209 @@ int orc_unpermute(const uint8_t *src, const int32_t *perm, int64_t n, int64_t ro
 {
     if (n < 0 || row_bytes < 0) return -1;
     for (int64_t p = 0; p < n; ++p) memcpy(dst + (int64_t)perm[p] * row_bytes, src + p * row_bytes, (size_t)row_bytes);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ in-bucket pooling
+ * (Section 4.2 "In-bucket Pooling"; Appendix "In-bucket Pooling")
+ *
+ * The bucket-major array is cut into tiles of `tile` consecutive rows (tiles start at a scan's first row
+ * and never span scans). Inside a tile of n rows, M = ceil(n / rho) sub-buckets of capacity rho are built
+ * in the Appendix's three steps, and each sub-bucket becomes one pooled row.
+ *
+ * The Appendix lets block-level atomics decide the order; as for Algorithms 1 and 2 the oracle fixes the
+ * index-ordered, round-synchronous schedule:
+ *   initial sub-buckets   each point hashes its voxel coordinate (relative to the tile's minimum, one of
+ *                         the four hash functions with M as the number of buckets) and the occupied hash
+ *                         values receive sub-bucket ids 0, 1, ... from the block counter in the order of
+ *                         their first (lowest-row) point. A sub-bucket keeps its first rho points.
+ *   new sub-buckets       the points beyond capacity, in row order, each open a new sub-bucket (next id
+ *                         of the counter) holding just that point, until the counter reaches M.
+ *   find new sub-bucket   the points still left repeat rounds: every one of them picks, from the state at
+ *                         the start of the round, the sub-bucket with room whose FIRST point is nearest to
+ *                         it (squared distance, binary32, ((dx*dx + dy*dy) + dz*dz), ties to the lower
+ *                         id); the contenders of a sub-bucket join in row order while it has room; the
+ *                         others try again next round. The text scans "newly allocated" sub-buckets; an
+ *                         initial sub-bucket that holds fewer than rho points has room just the same and
+ *                         is a candidate here, otherwise capacity could run out.
+ * M * rho >= n guarantees that every point is placed, and (M-1) * rho < n that all M sub-buckets exist.
+ *
+ * coords      [n,3] binary32, BUCKET-MAJOR rows
+ * row_offsets [n_scans+1] first row of every scan
+ * outputs: sub_of[n]  pooled row of every input row (global numbering: tiles in order, ids inside a tile)
+ *          slot_of[n] position of the row inside its sub-bucket (0 .. rho-1), may be NULL
+ *          step_of[n] 1 = initial, 2 = opened a new sub-bucket, 2 + r = joined in round r; may be NULL
+ *          pooled_offsets[n_scans+1] first pooled row of every scan; may be NULL
+ * returns the number of pooled rows, or -1 on bad arguments. */
+int64_t orc_pool_assign(const float *coords, const int32_t *row_offsets, int32_t n_scans, int32_t tile, int32_t rho,
+                        float voxel_size, int32_t hash, int32_t *sub_of, int32_t *slot_of, int32_t *step_of,
+                        int32_t *pooled_offsets)
+{
+    if (n_scans < 0 || tile < 1 || rho < 1 || !(voxel_size > 0.0f) || hash < 0 || hash > 3 || !sub_of) return -1;
+    const float inv = 1.0f / voxel_size;
+    int64_t out_base = 0;
+    int32_t *v = (int32_t *)malloc(sizeof(int32_t) * 3 * (size_t)tile);
+    int64_t *hv = (int64_t *)malloc(sizeof(int64_t) * (size_t)tile);
+    int32_t *id_of_hash = (int32_t *)malloc(sizeof(int32_t) * (size_t)tile);
+    int32_t *fill = (int32_t *)malloc(sizeof(int32_t) * (size_t)tile);
+    int32_t *first = (int32_t *)malloc(sizeof(int32_t) * (size_t)tile);   /* first point of a sub-bucket (local row) */
+    int32_t *sub = (int32_t *)malloc(sizeof(int32_t) * (size_t)tile);     /* -1 = not placed yet */
+    int32_t *pick = (int32_t *)malloc(sizeof(int32_t) * (size_t)tile);
+    int32_t *room = (int32_t *)malloc(sizeof(int32_t) * (size_t)tile);
+    for (int32_t b = 0; b < n_scans; ++b) {
+        if (pooled_offsets) pooled_offsets[b] = (int32_t)out_base;
+        for (int64_t t0 = row_offsets[b]; t0 < row_offsets[b + 1]; t0 += tile) {
+            const int64_t t1 = t0 + tile < row_offsets[b + 1] ? t0 + tile : row_offsets[b + 1];
+            const int32_t n = (int32_t)(t1 - t0);
+            const int32_t M = (n + rho - 1) / rho;
+            const float *c = coords + 3 * t0;
+            /* voxel coordinate inside the tile, as in Algorithm 1 line 4 */
+            float mn[3] = {c[0], c[1], c[2]};
+            for (int32_t i = 0; i < n; ++i)
+                for (int a = 0; a < 3; ++a)
+                    if (c[3 * i + a] < mn[a]) mn[a] = c[3 * i + a];
+            int32_t vmax[3] = {0, 0, 0};
+            for (int32_t i = 0; i < n; ++i)
+                for (int a = 0; a < 3; ++a) {
+                    volatile float d = c[3 * i + a] - mn[a];
+                    volatile float sc = d * inv;
+                    float f = floorf(sc);
+                    int32_t q = f >= (float)ORC_VOXEL_MAX ? ORC_VOXEL_MAX : (int32_t)f;
+                    if (q < 0) q = 0;
+                    v[3 * i + a] = q;
+                    if (q > vmax[a]) vmax[a] = q;
+                }
+            orc_hash_cfg cfg;
+            hash_cfg_fill(&cfg, hash, M, vmax, 0, 0);
+            for (int32_t i = 0; i < n; ++i) hv[i] = hash_bucket(&cfg, &v[3 * i]);
+
+            /* initial sub-buckets */
+            int32_t counter = 0;
+            for (int32_t h = 0; h < M; ++h) id_of_hash[h] = -1;
+            for (int32_t s = 0; s < M; ++s) fill[s] = 0;
+            for (int32_t i = 0; i < n; ++i) {
+                const int64_t h = hv[i];
+                if (id_of_hash[h] < 0) {
+                    id_of_hash[h] = counter;
+                    first[counter] = i;
+                    ++counter;
+                }
+                const int32_t s = id_of_hash[h];
+                sub[i] = -1;
+                if (fill[s] < rho) {
+                    sub[i] = s;
+                    if (slot_of) slot_of[t0 + i] = fill[s];
+                    if (step_of) step_of[t0 + i] = 1;
+                    ++fill[s];
+                }
+            }
+            /* new sub-bucket allocation */
+            for (int32_t i = 0; i < n && counter < M; ++i) {
+                if (sub[i] >= 0) continue;
+                const int32_t s = counter++;
+                first[s] = i;
+                fill[s] = 1;
+                sub[i] = s;
+                if (slot_of) slot_of[t0 + i] = 0;
+                if (step_of) step_of[t0 + i] = 2;
+            }
+            /* find new sub-bucket, in rounds */
+            for (int32_t round = 1;; ++round) {
+                int32_t left = 0;
+                for (int32_t s = 0; s < M; ++s) room[s] = rho - fill[s];
+                for (int32_t i = 0; i < n; ++i) {
+                    if (sub[i] >= 0) continue;
+                    ++left;
+                    int32_t best = -1;
+                    float bestd = 0.0f;
+                    for (int32_t s = 0; s < M; ++s) {
+                        if (room[s] <= 0) continue;
+                        const float *a = c + 3 * i, *f = c + 3 * first[s];
+                        volatile float dx = a[0] - f[0], dy = a[1] - f[1], dz = a[2] - f[2];
+                        volatile float xx = dx * dx, yy = dy * dy, zz = dz * dz;
+                        volatile float xy = xx + yy;
+                        const float d2 = xy + zz;
+                        if (best < 0 || d2 < bestd) { best = s; bestd = d2; }
+                    }
+                    pick[i] = best;
+                }
+                if (left == 0) break;
+                for (int32_t i = 0; i < n; ++i) {
+                    if (sub[i] >= 0) continue;
+                    const int32_t s = pick[i];
+                    if (s >= 0 && fill[s] < rho) {
+                        sub[i] = s;
+                        if (slot_of) slot_of[t0 + i] = fill[s];
+                        if (step_of) step_of[t0 + i] = 2 + round;
+                        ++fill[s];
+                    }
+                }
+                if (round > n + 1) break; /* cannot happen: every round places at least one point */
+            }
+            for (int32_t i = 0; i < n; ++i) sub_of[t0 + i] = (int32_t)(out_base + sub[i]);
+            out_base += M;
+        }
+    }
+    if (pooled_offsets) pooled_offsets[n_scans] = (int32_t)out_base;
+    free(room); free(pick); free(sub); free(first); free(fill); free(id_of_hash); free(hv); free(v);
+    return out_base;
+}
+
+/* binary64 -> bf16 with ONE rounding to nearest even (going through binary32 would round twice). */
+static uint16_t double_to_bf16(double x)
+{
+    if (x != x) return 0x7FC0;
+    float f = (float)x;
+    if (x != 0.0 && !isinf(x)) {
+        int e;
+        const double m = frexp(x, &e);              /* x = m * 2^e with 0.5 <= |m| < 1 */
+        int keep = 8;                               /* significant bits of a normal bf16 */
+        if (e - 1 < -126) keep -= -126 - (e - 1);   /* below the smallest normal exponent fewer bits remain */
+        if (keep < 0) keep = 0;
+        const double r = nearbyint(ldexp(m, keep)); /* default rounding mode: to nearest, ties to even */
+        f = (float)ldexp(r, e - keep);              /* exactly representable (or infinity on overflow) */
+    }
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    return (uint16_t)(u >> 16);
+}
+
+/* Reduce the rows of every sub-bucket (Section 4.2: sum, mean, min, max) in binary64 and round once to bf16.
+ * op: 0 sum, 1 mean, 2 min, 3 max. feat [n,C] bf16 bucket-major; sub_of [n]; out [n_out,C] bf16;
+ * counts [n_out] (may be NULL); coords [n,3] -> pooled_coords [n_out,3] = mean position in binary32 (both may be NULL). */
+int orc_pool_reduce(const uint16_t *feat, int64_t n, int32_t C, const int32_t *sub_of, int64_t n_out, int32_t op,
+                    uint16_t *out, int32_t *counts, const float *coords, float *pooled_coords)
+{
+    if (n < 0 || C < 1 || n_out < 0 || op < 0 || op > 3) return -1;
+    double *acc = (double *)malloc(sizeof(double) * (size_t)(n_out > 0 ? n_out : 1) * (size_t)C);
+    double *cacc = (double *)calloc((size_t)(n_out > 0 ? n_out : 1) * 3, sizeof(double));
+    int32_t *cnt = (int32_t *)calloc((size_t)(n_out > 0 ? n_out : 1), sizeof(int32_t));
+    for (int64_t p = 0; p < n; ++p) {
+        const int64_t s = sub_of[p];
+        if (s < 0 || s >= n_out) { free(acc); free(cacc); free(cnt); return -1; }
+        for (int32_t ch = 0; ch < C; ++ch) {
+            const double x = bf16_to_double(feat[p * C + ch]);
+            double *a = &acc[s * C + ch];
+            if (cnt[s] == 0) *a = x;
+            else if (op <= 1) *a += x;
+            else if (op == 2) *a = x < *a ? x : *a;
+            else *a = x > *a ? x : *a;
+        }
+        if (coords)
+            for (int a = 0; a < 3; ++a) cacc[s * 3 + a] += (double)coords[3 * p + a];
+        ++cnt[s];
+    }
+    for (int64_t s = 0; s < n_out; ++s) {
+        for (int32_t ch = 0; ch < C; ++ch) {
+            double x = cnt[s] ? acc[s * C + ch] : 0.0;
+            if (op == 1 && cnt[s]) x /= (double)cnt[s];
+            out[s * C + ch] = double_to_bf16(x);
+        }
+        if (pooled_coords)
+            for (int a = 0; a < 3; ++a) pooled_coords[s * 3 + a] = cnt[s] ? (float)(cacc[s * 3 + a] / (double)cnt[s]) : 0.0f;
+        if (counts) counts[s] = cnt[s];
+    }
+    free(acc); free(cacc); free(cnt);
     return 0;
 }
 
