@@ -155,6 +155,48 @@ int f3d_bucket_swin_attn(const void *q, const void *k, const void *v, const int3
                          int32_t head_dim, float softmax_scale, void *out, const int32_t *out_perm, void *stream);
 
 /*
+ * In-bucket pooling (Section 4.2 "In-bucket Pooling"; Appendix "In-bucket Pooling"): the bucket-major array is
+ * cut into tiles of `tile` consecutive rows (tiles start at a scan's first row and never span scans); inside a
+ * tile of n rows, M = ceil(n / rho) sub-buckets of capacity rho are built in the Appendix's three steps (initial
+ * sub-buckets from a hash of the voxel coordinate relative to the tile's minimum, new sub-buckets for the rows
+ * beyond capacity until M exist, rounds in which the rows still left join the sub-bucket with room whose first
+ * row is nearest), and every sub-bucket is reduced to one pooled row. The block-level atomics of the Appendix are
+ * replaced by decisions in row order, so the result is a function of the input alone. Pooled rows are numbered
+ * tile by tile, sub-bucket ids inside a tile; every sub-bucket holds between 1 and rho rows.
+ *
+ *   coords        [n,3] binary32: input order if perm is given (row p is read from perm[p]), else bucket-major
+ *   perm          NULL or [n] as written by f3d_psh_bucketize
+ *   feat          bf16 [n, channels] BUCKET-MAJOR rows (what f3d_bucket_swin_attn writes), 16-byte aligned
+ *   batch_offsets [n_scans+1] int32 device array as for f3d_psh_bucketize (scans keep their row ranges), NULL = one scan
+ *   channels      multiple of 8
+ *   tile          1 .. 1024 rows;  rho  1 .. 64, the pooling factor and sub-bucket capacity
+ *   voxel_size    > 0, edge of the voxels the in-tile hash works on;  hash  F3D_HASH_*
+ *   op            F3D_POOL_SUM | F3D_POOL_MEAN | F3D_POOL_MIN | F3D_POOL_MAX
+ *   pooled_feat (out)   bf16 [f3d_pool_max_rows(), channels]; fp32 accumulation in slot order, one rounding to bf16
+ *   pooled_coords (out) [f3d_pool_max_rows(), 3] binary32 mean position of every pooled row; may be NULL
+ *   sub_of (out)        [n] pooled row of every bucket-major input row; may be NULL
+ *   pooled_offsets (out) [n_scans+1] first pooled row of every scan; last entry = number of pooled rows, or -1
+ *                       if batch_offsets was inconsistent (then nothing else is written)
+ *   workspace           >= f3d_pool_workspace_bytes(), 256-byte aligned
+ */
+#define F3D_POOL_SUM 0
+#define F3D_POOL_MEAN 1
+#define F3D_POOL_MIN 2
+#define F3D_POOL_MAX 3
+#define F3D_POOL_MAX_TILE 1024
+#define F3D_POOL_MAX_RHO 64
+
+/* Upper bound on the number of pooled rows, known on the host: n / rho + n / tile + n_scans + 1; -1 on bad arguments. */
+int64_t f3d_pool_max_rows(int64_t n, int32_t n_scans, int32_t tile, int32_t rho);
+
+int f3d_pool_workspace_bytes(int64_t n, int32_t n_scans, int32_t tile, size_t *out_bytes);
+
+int f3d_inbucket_pool(const float *coords, const int32_t *perm, const void *feat, const int32_t *batch_offsets,
+                      int64_t n, int32_t n_scans, int32_t channels, int32_t tile, int32_t rho, float voxel_size,
+                      int32_t hash, int32_t op, void *pooled_feat, float *pooled_coords, int32_t *sub_of,
+                      int32_t *pooled_offsets, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Inverse of the up-front scatter (Section 4, "up-front global shuffle"): dst[perm[p], :] = src[p, :].
  *   src, dst  [n, row_bytes] bytes; row_bytes > 0 and a multiple of 4; src != dst; 4-byte aligned
  *             (16-byte aligned rows take the wide path)

@@ -21,7 +21,9 @@ MODES = {"plain": 0, "shift": 1, "stride": 2}
 SCHEDULES = {"auto": 0, "general": 1, "steps": 2}
 
 EXPORTS = ("f3d_params_default", "f3d_max_buckets", "f3d_workspace_bytes", "f3d_psh_bucketize",
-           "f3d_bucket_swin_attn", "f3d_unpermute", "f3d_error_string", "f3d_last_hip_error", "f3d_version")
+           "f3d_bucket_swin_attn", "f3d_pool_max_rows", "f3d_pool_workspace_bytes", "f3d_inbucket_pool",
+           "f3d_unpermute", "f3d_error_string", "f3d_last_hip_error", "f3d_version")
+POOL_OPS = {"sum": 0, "mean": 1, "min": 2, "max": 3}
 
 
 class f3d_params(ctypes.Structure):
@@ -65,6 +67,13 @@ def lib() -> ctypes.CDLL:
         L.f3d_psh_bucketize.restype = ctypes.c_int
         L.f3d_bucket_swin_attn.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, i32, i32, i32, i32, i32, i32, f32, vp, vp, vp]
         L.f3d_bucket_swin_attn.restype = ctypes.c_int
+        L.f3d_pool_max_rows.argtypes = [i64, i32, i32, i32]
+        L.f3d_pool_max_rows.restype = i64
+        L.f3d_pool_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(ctypes.c_size_t)]
+        L.f3d_pool_workspace_bytes.restype = ctypes.c_int
+        L.f3d_inbucket_pool.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, i32, f32, i32, i32, vp, vp, vp, vp, vp,
+                                        ctypes.c_size_t, vp]
+        L.f3d_inbucket_pool.restype = ctypes.c_int
         L.f3d_unpermute.argtypes = [vp, vp, i64, i32, vp, vp]
         L.f3d_unpermute.restype = ctypes.c_int
         L.f3d_error_string.argtypes = [ctypes.c_int]
@@ -179,6 +188,52 @@ def bucket_swin_attn(q, k, v, buckets: Buckets, heads: int, head_dim: int, mode:
                                     _ptr(buckets.perm) if original_order else None, _stream())
     if rc != F3D_OK:
         raise Flash3DError(rc, "f3d_bucket_swin_attn")
+    return out
+
+
+@dataclass
+class Pooled:
+    """Outputs of f3d_inbucket_pool (torch tensors on the GPU); rows past pooled_offsets[-1] are unspecified."""
+    feat: object            # bfloat16 [max_rows, C]
+    coords: object          # float32 [max_rows, 3]
+    sub_of: object          # int32 [n]
+    pooled_offsets: object  # int32 [n_scans + 1]
+    max_rows: int
+
+
+def pool_max_rows(n: int, n_scans: int, tile: int, rho: int) -> int:
+    r = int(lib().f3d_pool_max_rows(n, n_scans, tile, rho))
+    if r < 0:
+        raise Flash3DError(ERR_INVALID_ARG, "f3d_pool_max_rows")
+    return r
+
+
+def inbucket_pool(coords, perm, feat, batch_offsets, tile: int, rho: int, voxel_size: float, hash: str = "zorder_div",
+                  op: str = "mean", workspace=None, out: Optional[Pooled] = None) -> Pooled:
+    """f3d_inbucket_pool on torch CUDA tensors. coords float32 [n,3] (input order with perm, else bucket-major);
+    feat bfloat16 [n,C] bucket-major; batch_offsets int32 [n_scans+1] or None."""
+    import torch
+    n, C = int(feat.shape[0]), int(feat.shape[1])
+    assert coords.is_cuda and coords.dtype == torch.float32 and coords.is_contiguous() and coords.shape == (n, 3)
+    assert feat.is_cuda and feat.dtype == torch.bfloat16 and feat.is_contiguous()
+    n_scans = 1 if batch_offsets is None else int(batch_offsets.shape[0]) - 1
+    dev = feat.device
+    if out is None:
+        mr = pool_max_rows(n, n_scans, tile, rho)
+        out = Pooled(torch.empty(mr, C, dtype=torch.bfloat16, device=dev), torch.empty(mr, 3, dtype=torch.float32, device=dev),
+                     torch.empty(n, dtype=torch.int32, device=dev), torch.empty(n_scans + 1, dtype=torch.int32, device=dev), mr)
+    if workspace is None:
+        nb = ctypes.c_size_t(0)
+        rc = lib().f3d_pool_workspace_bytes(n, n_scans, tile, ctypes.byref(nb))
+        if rc != F3D_OK:
+            raise Flash3DError(rc, "f3d_pool_workspace_bytes")
+        workspace = torch.empty(max(int(nb.value), 256), dtype=torch.uint8, device=dev)
+    rc = lib().f3d_inbucket_pool(_ptr(coords), _ptr(perm), _ptr(feat), _ptr(batch_offsets), n, n_scans, C, tile, rho,
+                                 voxel_size, HASHES[hash] if isinstance(hash, str) else int(hash),
+                                 POOL_OPS[op] if isinstance(op, str) else int(op), _ptr(out.feat), _ptr(out.coords),
+                                 _ptr(out.sub_of), _ptr(out.pooled_offsets), _ptr(workspace), workspace.numel(), _stream())
+    if rc != F3D_OK:
+        raise Flash3DError(rc, "f3d_inbucket_pool")
     return out
 
 

@@ -7,6 +7,7 @@
 
 #include "attn.h"
 #include "flash3d.h"
+#include "pool.h"
 #include "psh.h"
 
 namespace {
@@ -254,6 +255,76 @@ int f3d_bucket_swin_attn(const void* q, const void* k, const void* v, const int3
     a.n_slots = (int)slots;
     (void)hipGetLastError();
     const hipError_t e = f3d::attn_launch(a, head_dim, bm, (hipStream_t)stream);
+    return e == hipSuccess ? F3D_OK : hip_fail(e);
+}
+
+static int check_pool(int64_t n, int32_t n_scans, int32_t tile, int32_t rho)
+{
+    if (n < 0 || n_scans < 1 || tile < 1 || rho < 1) return F3D_ERR_INVALID_ARG;
+    if (tile > F3D_POOL_MAX_TILE || rho > F3D_POOL_MAX_RHO) return F3D_ERR_UNSUPPORTED;
+    if (n >= (int64_t)2147483647 - (1 << 20) || n_scans > 65535) return F3D_ERR_UNSUPPORTED;
+    return F3D_OK;
+}
+
+int64_t f3d_pool_max_rows(int64_t n, int32_t n_scans, int32_t tile, int32_t rho)
+{
+    if (check_pool(n, n_scans, tile, rho) != F3D_OK) return -1;
+    return n / rho + n / tile + n_scans + 1;
+}
+
+int f3d_pool_workspace_bytes(int64_t n, int32_t n_scans, int32_t tile, size_t* out_bytes)
+{
+    if (!out_bytes) return F3D_ERR_INVALID_ARG;
+    const int rc = check_pool(n, n_scans, tile, 1);
+    if (rc != F3D_OK) return rc;
+    *out_bytes = align_up((size_t)(n / tile + n_scans) * sizeof(int4), 256);
+    return F3D_OK;
+}
+
+int f3d_inbucket_pool(const float* coords, const int32_t* perm, const void* feat, const int32_t* batch_offsets, int64_t n,
+                      int32_t n_scans, int32_t channels, int32_t tile, int32_t rho, float voxel_size, int32_t hash, int32_t op,
+                      void* pooled_feat, float* pooled_coords, int32_t* sub_of, int32_t* pooled_offsets, void* workspace,
+                      size_t workspace_bytes, void* stream)
+{
+    const int rc = check_pool(n, n_scans, tile, rho);
+    if (rc != F3D_OK) return rc;
+    if (channels < 8 || channels % 8 != 0) return F3D_ERR_INVALID_ARG;
+    if (!(voxel_size > 0.0f) || !isfinite(voxel_size)) return F3D_ERR_INVALID_ARG;
+    if (hash < 0 || hash > 3 || op < F3D_POOL_SUM || op > F3D_POOL_MAX) return F3D_ERR_INVALID_ARG;
+    if (!pooled_offsets || !workspace) return F3D_ERR_INVALID_ARG;
+    if (n > 0 && (!coords || !feat || !pooled_feat)) return F3D_ERR_INVALID_ARG;
+    if (((uintptr_t)coords | (uintptr_t)perm | (uintptr_t)batch_offsets | (uintptr_t)pooled_coords | (uintptr_t)sub_of |
+         (uintptr_t)pooled_offsets) & 3)
+        return F3D_ERR_BAD_ALIGNMENT;
+    if (((uintptr_t)feat | (uintptr_t)pooled_feat) & 15) return F3D_ERR_BAD_ALIGNMENT;
+    if ((uintptr_t)workspace & 255) return F3D_ERR_BAD_ALIGNMENT;
+    size_t need = 0;
+    f3d_pool_workspace_bytes(n, n_scans, tile, &need);
+    if (workspace_bytes < need) return F3D_ERR_WORKSPACE_TOO_SMALL;
+
+    f3d::PoolArgs a;
+    memset(&a, 0, sizeof(a));
+    a.coords = coords;
+    a.perm = perm;
+    a.feat = (const uint16_t*)feat;
+    a.batch_offsets = batch_offsets;
+    a.n = (int)n;
+    a.n_scans = n_scans;
+    a.C = channels;
+    a.tile = tile;
+    a.rho = rho;
+    a.inv_voxel = 1.0f / voxel_size;
+    a.hash = hash;
+    a.op = op;
+    a.kp = ((tile + rho - 1) / rho + 63) / 64 * 64;
+    a.n_tiles_ub = (int)(n / tile) + n_scans;
+    a.pooled_feat = (uint16_t*)pooled_feat;
+    a.pooled_coords = pooled_coords;
+    a.sub_of = sub_of;
+    a.pooled_offsets = pooled_offsets;
+    a.tile_info = (int4*)workspace;
+    (void)hipGetLastError();
+    const hipError_t e = f3d::pool_launch(a, (hipStream_t)stream);
     return e == hipSuccess ? F3D_OK : hip_fail(e);
 }
 

@@ -1,0 +1,375 @@
+// In-bucket pooling (Section 4.2 "In-bucket Pooling"; Appendix "In-bucket Pooling") for gfx950.
+//
+// The bucket-major array is cut into tiles of up to 1024 consecutive rows of one scan; one workgroup of
+// 1024 threads (a thread per row) builds the tile's M = ceil(n / rho) sub-buckets entirely in LDS, in the
+// Appendix's three steps (initial sub-buckets from a hash of the voxel coordinate, new sub-buckets for the
+// points beyond capacity until the block counter reaches M, rounds in which the points still left join the
+// nearest sub-bucket with room), then reduces the feature rows of every sub-bucket and writes the pooled rows
+// of the tile as one contiguous piece.
+//
+// The Appendix decides who comes first with block-level atomics. Here every such decision is taken in row
+// order (stable ranks from wave ballots plus per-wave counters, as in the bucketing kernels), so the result
+// is a function of the input alone.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pool.h"
+#include "psh_common.h"
+
+namespace f3d {
+
+namespace {
+
+constexpr int PT = POOL_MAX_TILE;   // threads per workgroup = most rows of a tile
+constexpr int PW = PT / 64;
+
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    f32x2 x = {lo, hi};
+    bf16x2 y = __builtin_convertvector(x, bf16x2);  // round to nearest even
+    return *reinterpret_cast<uint32_t*>(&y);
+}
+
+__device__ __forceinline__ int pool_batch_off(const PoolArgs& a, int b)
+{
+    if (a.batch_offsets) return a.batch_offsets[b];
+    return b == 0 ? 0 : a.n;
+}
+
+// ------------------------------------------------------------------------------------------------
+// tile table and pooled-row offsets of every scan (one workgroup)
+__global__ __launch_bounds__(1024) void k_pool_meta(PoolArgs a)
+{
+    __shared__ int lds[17];
+    __shared__ int bad;
+    const int tid = threadIdx.x;
+    if (tid == 0) bad = 0;
+    __syncthreads();
+    const int per_full = (a.tile + a.rho - 1) / a.rho;   // pooled rows of a full tile
+    int tcarry = 0, ocarry = 0;
+    for (int base = 0; base < a.n_scans; base += 1024) {
+        const int b = base + tid;
+        int tiles = 0, rows = 0, p0 = 0, nb = 0;
+        if (b < a.n_scans) {
+            p0 = pool_batch_off(a, b);
+            const int p1 = pool_batch_off(a, b + 1);
+            nb = p1 - p0;
+            bool ok = nb >= 0 && p0 >= 0 && p1 <= a.n;
+            if (b == 0 && p0 != 0) ok = false;
+            if (b == a.n_scans - 1 && p1 != a.n) ok = false;
+            if (!ok) { bad = 1; nb = 0; }
+            if (nb > 0) {
+                tiles = (nb + a.tile - 1) / a.tile;
+                const int last = nb - (tiles - 1) * a.tile;
+                rows = (tiles - 1) * per_full + (last + a.rho - 1) / a.rho;
+            }
+        }
+        int ttot, otot;
+        const int tpre = block_excl_scan(tiles, &ttot, lds);
+        const int opre = block_excl_scan(rows, &otot, lds);
+        if (b < a.n_scans) {
+            a.pooled_offsets[b] = ocarry + opre;
+            for (int t = 0; t < tiles && tcarry + tpre + t < a.n_tiles_ub; ++t) {   // scans are spread over the threads
+                const int r0 = p0 + t * a.tile;
+                a.tile_info[tcarry + tpre + t] = make_int4(r0, min(a.tile, p0 + nb - r0), ocarry + opre + t * per_full, b);
+            }
+        }
+        tcarry += ttot;
+        ocarry += otot;
+    }
+    __syncthreads();
+    const int isbad = bad;
+    if (tid == 0) a.pooled_offsets[a.n_scans] = isbad ? -1 : ocarry;
+    // with inconsistent offsets no tile is processed at all
+    for (int t = (isbad ? 0 : min(tcarry, a.n_tiles_ub)) + tid; t < a.n_tiles_ub; t += 1024) a.tile_info[t] = make_int4(0, 0, 0, -1);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Rank of every active thread among the active threads of the workgroup that hold the same key, in thread
+// order. wcnt [PW][kp] is scratch; when ktot is given, ktot[k] = number of active threads with key k, k < nkeys.
+__device__ __forceinline__ int block_rank_by_key(int key, bool active, int keybits, int nkeys, uint16_t* wcnt, int kp,
+                                                 uint16_t* ktot)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int w = tid; w < PW * kp / 2; w += PT) reinterpret_cast<uint32_t*>(wcnt)[w] = 0u;
+    __syncthreads();
+    const unsigned long long m = match_key(key, active, keybits);
+    const int before = __popcll(m & ((1ull << lane) - 1ull));
+    if (active && before == 0) wcnt[wave * kp + key] = (uint16_t)__popcll(m);
+    __syncthreads();
+    for (int k = tid; k < nkeys; k += PT) {   // exclusive prefix over the waves
+        int run = 0;
+#pragma unroll
+        for (int w = 0; w < PW; ++w) {
+            const int c = wcnt[w * kp + k];
+            wcnt[w * kp + k] = (uint16_t)run;
+            run += c;
+        }
+        if (ktot) ktot[k] = (uint16_t)run;
+    }
+    __syncthreads();
+    return active ? (int)wcnt[wave * kp + key] + before : 0;
+}
+
+// hash setting of a tile: M sub-buckets, voxel box vmax (automatic divisor as for the main hash, Section 4.1)
+__device__ inline void tile_hash_cfg(int hash, int M, const int* vmax, ScanCfg& c)
+{
+    const int K = max(M, 1);
+    c.K = K;
+    int vm = 0;
+    for (int ax = 0; ax < 3; ++ax) {
+        c.vmax[ax] = vmax[ax];
+        vm = max(vm, vmax[ax]);
+    }
+    const int nbits = max(1, bit_width64((unsigned long long)vm));
+    c.invK = 1.0 / (double)K;
+    unsigned long long D = 1;
+    if (hash == 1) D = udiv63_small((1ull << nbits) - 1, K, c.invK) + 1;
+    if (hash == 3) D = udiv63_small(morton3(vmax[0], vmax[1], vmax[2]), K, c.invK) + 1;
+    c.D = D;
+    c.invD = 1.0 / (double)D;
+    c.m32 = umod52(4294967296ull, K, c.invK);
+    c.step = 1;
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// dynamic LDS, kp = a.kp: px,py,pz [PT] floats | ox,oy,oz [kp] floats | fill [kp] ints | wcnt [PW][kp] u16 |
+// open_list, id_of_hash, first_idx, ktot [kp] u16 each | members [PT + POOL_MAX_RHO] u16
+__global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    __shared__ int lds[17];
+    __shared__ uint32_t red[8];
+    __shared__ ScanCfg cfg;
+    const int4 ti = a.tile_info[blockIdx.x];
+    const int n = ti.y;
+    if (n <= 0) return;
+    const int row0 = ti.x, out0 = ti.z;
+    const int rho = a.rho, kp = a.kp;
+    const int M = (n + rho - 1) / rho;
+    const int tid = threadIdx.x, lane = tid & 63;
+    float* px = reinterpret_cast<float*>(smem);
+    float* py = px + PT;
+    float* pz = py + PT;
+    float* ox = pz + PT;
+    float* oy = ox + kp;
+    float* oz = oy + kp;
+    int* fill = reinterpret_cast<int*>(oz + kp);
+    uint16_t* wcnt = reinterpret_cast<uint16_t*>(fill + kp);
+    uint16_t* open_list = wcnt + PW * kp;
+    uint16_t* id_of_hash = open_list + kp;
+    uint16_t* first_idx = id_of_hash + kp;
+    uint16_t* ktot = first_idx + kp;
+    uint16_t* members = ktot + kp;
+
+    // ---- the tile's points, its minimum, voxel coordinates, voxel box
+    const bool act = tid < n;
+    float x = 0.f, y = 0.f, z = 0.f;
+    if (act) {
+        const size_t src = a.perm ? (size_t)a.perm[row0 + tid] : (size_t)(row0 + tid);
+        x = a.coords[3 * src];
+        y = a.coords[3 * src + 1];
+        z = a.coords[3 * src + 2];
+        px[tid] = x;
+        py[tid] = y;
+        pz[tid] = z;
+    }
+    if (tid < 3) { red[tid] = 0xFFFFFFFFu; red[4 + tid] = 0u; }
+    for (int k = tid; k < kp; k += PT) {
+        fill[k] = 0;
+        first_idx[k] = 0;
+    }
+    __syncthreads();
+    {
+        uint32_t o[3] = {act ? f2ord(x) : 0xFFFFFFFFu, act ? f2ord(y) : 0xFFFFFFFFu, act ? f2ord(z) : 0xFFFFFFFFu};
+#pragma unroll
+        for (int ax = 0; ax < 3; ++ax) {
+            uint32_t lo = o[ax];
+            for (int d = 32; d >= 1; d >>= 1) lo = min(lo, (uint32_t)__shfl_xor((int)lo, d, 64));
+            if (lane == 0) atomicMin(&red[ax], lo);
+        }
+    }
+    __syncthreads();
+    const float mnx = ord2f(red[0]), mny = ord2f(red[1]), mnz = ord2f(red[2]);
+    int vx = 0, vy = 0, vz = 0;
+    if (act) {
+        vx = voxel_of(x, mnx, a.inv_voxel);
+        vy = voxel_of(y, mny, a.inv_voxel);
+        vz = voxel_of(z, mnz, a.inv_voxel);
+    }
+    {
+        int v[3] = {vx, vy, vz};
+#pragma unroll
+        for (int ax = 0; ax < 3; ++ax) {
+            int hi = v[ax];
+            for (int d = 32; d >= 1; d >>= 1) hi = max(hi, __shfl_xor(hi, d, 64));
+            if (lane == 0) atomicMax(&red[4 + ax], (uint32_t)hi);
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        const int vmax[3] = {(int)red[4], (int)red[5], (int)red[6]};
+        tile_hash_cfg(a.hash, M, vmax, cfg);
+    }
+    __syncthreads();
+    const int h = act ? hash_bucket(a.hash, vx, vy, vz, cfg) : 0;
+    const int keybits = max(1, 32 - __clz(max(M - 1, 1)));
+
+    // ---- initial sub-buckets: occupied hash values get ids in the order of their first row; a sub-bucket keeps
+    //      its first rho rows
+    const int r = block_rank_by_key(h, act, keybits, M, wcnt, kp, ktot);
+    const bool is_first = act && r == 0;
+    int A;
+    const int id = block_excl_scan(is_first ? 1 : 0, &A, lds);
+    if (is_first) {
+        id_of_hash[h] = (uint16_t)id;
+        first_idx[id] = (uint16_t)tid;
+        fill[id] = min((int)ktot[h], rho);
+    }
+    __syncthreads();
+    int sub = -1, slot = 0;
+    if (act && r < rho) {
+        sub = id_of_hash[h];
+        slot = r;
+    }
+    // ---- new sub-buckets: the rows beyond capacity, in row order, open one each until the counter reaches M
+    const bool overflow = act && sub < 0;
+    int nov;
+    const int orank = block_excl_scan(overflow ? 1 : 0, &nov, lds);
+    if (overflow && A + orank < M) {
+        sub = A + orank;
+        slot = 0;
+        fill[sub] = 1;
+        first_idx[sub] = (uint16_t)tid;
+    }
+    bool left = act && sub < 0;
+    // ---- rounds: every row still left picks the open sub-bucket whose first row is nearest (state at the start of
+    //      the round); the contenders of a sub-bucket join in row order while it has room
+    for (int round = 0; round <= PT; ++round) {   // every round places at least one row; the bound is a safeguard
+        if (!__syncthreads_or(left ? 1 : 0)) break;
+        const bool open = tid < M && fill[tid] < rho;
+        int nopen;
+        const int pos = block_excl_scan(open ? 1 : 0, &nopen, lds);
+        if (open) {
+            const int f = first_idx[tid];
+            open_list[pos] = (uint16_t)tid;
+            ox[pos] = px[f];
+            oy[pos] = py[f];
+            oz[pos] = pz[f];
+        }
+        __syncthreads();
+        int best = 0, bj = -1;
+        if (left) {
+            float bd = 0.f;
+            for (int j = 0; j < nopen; ++j) {   // ascending sub-bucket id: a tie keeps the lower id
+                const float dx = __fsub_rn(x, ox[j]), dy = __fsub_rn(y, oy[j]), dz = __fsub_rn(z, oz[j]);
+                const float d2 = __fadd_rn(__fadd_rn(__fmul_rn(dx, dx), __fmul_rn(dy, dy)), __fmul_rn(dz, dz));
+                if (bj < 0 || d2 < bd) { bd = d2; bj = j; }
+            }
+            if (bj >= 0) best = open_list[bj];
+        }
+        const int rank = block_rank_by_key(best, left, keybits, M, wcnt, kp, nullptr);
+        const bool join = left && bj >= 0 && fill[best] + rank < rho;
+        if (join) {
+            sub = best;
+            slot = fill[best] + rank;
+        }
+        __syncthreads();   // every fill level has been read
+        if (join) atomicAdd(&fill[best], 1);
+        left = left && !join;
+    }
+
+    // ---- members of every sub-bucket by slot, the map row -> pooled row
+    if (act && sub >= 0) {
+        members[sub * rho + slot] = (uint16_t)tid;
+        if (a.sub_of) a.sub_of[row0 + tid] = out0 + sub;
+    }
+    __syncthreads();
+    // ---- reduce: one (sub-bucket, 16-byte column) per thread and pass; rows are added in slot order
+    const int NCH = a.C >> 3;
+    const uint4* feat = reinterpret_cast<const uint4*>(a.feat);
+    uint4* outp = reinterpret_cast<uint4*>(a.pooled_feat);
+    const int op = a.op;
+    for (int idx = tid; idx < M * NCH; idx += PT) {
+        const int s = idx / NCH, ch = idx - s * NCH;
+        const int cnt = fill[s];
+        float acc[8];
+        for (int sl = 0; sl < cnt; ++sl) {
+            const int rr = min((int)members[s * rho + sl], n - 1);
+            const uint4 v = feat[(size_t)(row0 + rr) * NCH + ch];
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float lo = bf16_lo(w[e]), hi = bf16_hi(w[e]);
+                if (sl == 0) {
+                    acc[2 * e] = lo;
+                    acc[2 * e + 1] = hi;
+                } else if (op <= 1) {
+                    acc[2 * e] += lo;
+                    acc[2 * e + 1] += hi;
+                } else if (op == 2) {
+                    acc[2 * e] = fminf(acc[2 * e], lo);
+                    acc[2 * e + 1] = fminf(acc[2 * e + 1], hi);
+                } else {
+                    acc[2 * e] = fmaxf(acc[2 * e], lo);
+                    acc[2 * e + 1] = fmaxf(acc[2 * e + 1], hi);
+                }
+            }
+        }
+        if (op == 1) {
+            const float c = (float)cnt;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] = acc[e] / c;
+        }
+        uint4 o;
+        o.x = pack_bf16(acc[0], acc[1]);
+        o.y = pack_bf16(acc[2], acc[3]);
+        o.z = pack_bf16(acc[4], acc[5]);
+        o.w = pack_bf16(acc[6], acc[7]);
+        outp[(size_t)(out0 + s) * NCH + ch] = o;
+    }
+    // ---- pooled position: mean of the members' coordinates
+    if (a.pooled_coords && tid < M) {
+        const int cnt = fill[tid];
+        float sx = 0.f, sy = 0.f, sz = 0.f;
+        for (int sl = 0; sl < cnt; ++sl) {
+            const int rr = min((int)members[tid * rho + sl], n - 1);
+            sx += px[rr];
+            sy += py[rr];
+            sz += pz[rr];
+        }
+        const float c = (float)cnt;
+        float* dst = a.pooled_coords + (size_t)(out0 + tid) * 3;
+        dst[0] = sx / c;
+        dst[1] = sy / c;
+        dst[2] = sz / c;
+    }
+}
+
+size_t pool_lds_bytes(int kp)
+{
+    return (size_t)3 * PT * 4 + (size_t)3 * kp * 4 + (size_t)kp * 4 + (size_t)PW * kp * 2 + (size_t)4 * kp * 2 +
+           (size_t)(PT + POOL_MAX_RHO) * 2;
+}
+
+}  // namespace
+
+hipError_t pool_launch(const PoolArgs& a, hipStream_t stream)
+{
+    k_pool_meta<<<1, 1024, 0, stream>>>(a);
+    if (a.n == 0) return hipGetLastError();
+    const size_t lds = pool_lds_bytes(a.kp);
+    if (lds > 60000) {
+        const hipError_t e = hipFuncSetAttribute((const void*)k_pool, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    k_pool<<<a.n_tiles_ub, PT, lds, stream>>>(a);
+    return hipGetLastError();
+}
+
+}  // namespace f3d

@@ -345,3 +345,100 @@ def test_attention_stores_in_input_order_on_request(name, bucket_major):
         fused = f3d.bucket_swin_attn(q, k, v, bk, w.heads, w.head_dim, mode, 2, 2, not bucket_major, original_order=True)
         torch.cuda.synchronize()
         assert torch.equal(fused, two_step)
+
+
+# ----------------------------------------------------------------------------- in-bucket pooling
+
+
+def bf16_ulp(x):
+    """Spacing of bf16 at |x| (8 significant bits), with a floor for values near zero."""
+    e = np.floor(np.log2(np.maximum(np.abs(x), 2.0 ** -20)))
+    return 2.0 ** (e - 7)
+
+
+def check_pool(coords_in, perm, feat_bm_bits, bo, tile, rho, voxel, hash="zorder_div", op="mean"):
+    """GPU pooling against the oracle: the row -> pooled row map and the offsets bit for bit; min/max rows bit for
+    bit; sum/mean rows within one bf16 spacing of the binary64 result (fp32 accumulation of at most rho terms can
+    move a value across a rounding boundary, never further); positions to 1e-5 of the coordinate range."""
+    n = feat_bm_bits.shape[0]
+    coords_bm = coords_in if perm is None else coords_in[perm]
+    ro = np.array([0, n], dtype=np.int32) if bo is None else bo.astype(np.int32)
+    ref = oracle.pool_assign(coords_bm, ro, tile, rho, voxel, hash)
+    want = oracle.pool_reduce(feat_bm_bits, ref["sub_of"], ref["n_out"], op, coords_bm)
+    got = f3d.inbucket_pool(dev(coords_in), None if perm is None else dev(perm), dev(feat_bm_bits, torch.bfloat16),
+                            None if bo is None else dev(bo.astype(np.int32)), tile, rho, voxel, hash, op)
+    torch.cuda.synchronize()
+    n_out = ref["n_out"]
+    assert got.pooled_offsets.cpu().numpy().tolist() == ref["pooled_offsets"].tolist()
+    assert np.array_equal(got.sub_of.cpu().numpy(), ref["sub_of"])
+    g = got.feat[:n_out].float().cpu().numpy().astype(np.float64)
+    w = wl.bf16_bits_to_f32(want["feat"]).astype(np.float64)
+    if op in ("min", "max"):
+        assert np.array_equal(got.feat[:n_out].view(torch.int16).cpu().numpy().view(np.uint16), want["feat"])
+    else:
+        assert (np.abs(g - w) <= bf16_ulp(w)).all(), f"max deviation {np.abs(g - w).max()}"
+        assert (np.abs(g - w) > 0).mean() < 0.02           # and almost every value is the correctly rounded one
+    span = float(np.abs(coords_bm).max()) if n else 1.0
+    assert np.abs(got.coords[:n_out].cpu().numpy() - want["coords"]).max(initial=0.0) <= 1e-5 * span
+    return ref
+
+
+@pytest.mark.parametrize("hash", HASHES)
+@pytest.mark.parametrize("rho,op", [(2, "mean"), (4, "max"), (3, "sum"), (8, "min")])
+def test_pool_matches_oracle_on_the_indoor_layout(hash, rho, op):
+    w = wl.make_workload("indoor")
+    bk = run_bucketize(w.coords, w.batch_offsets, w.voxel_size, w.bucket_cap)
+    perm = bk.perm.cpu().numpy()
+    rng = np.random.default_rng(40)
+    feat = wl.f32_to_bf16_bits(rng.standard_normal((w.n, 64)).astype(np.float32))
+    check_pool(w.coords, perm, feat, w.batch_offsets, 1024, rho, 0.1, hash, op)
+
+
+def test_pool_on_scans_with_ragged_tiles_and_bucket_major_coordinates():
+    rng = np.random.default_rng(41)
+    sizes = [1, 1023, 1024, 1025, 0, 3000, 77, 0, 5]
+    bo = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    n = int(bo[-1])
+    c = np.concatenate([wl.uniform_cube(rng, s, 1.0 + i) + 10.0 * i for i, s in enumerate(sizes)]).astype(np.float32)
+    feat = wl.f32_to_bf16_bits(rng.standard_normal((n, 32)).astype(np.float32))
+    for tile, rho in ((1024, 2), (512, 4), (100, 3), (64, 1), (1000, 64)):
+        check_pool(c, None, feat, bo, tile, rho, 0.05, "zorder_div", "mean")
+        check_pool(c, None, feat, bo, tile, rho, 0.3, "xor_mod", "max")
+
+
+def test_pool_dense_clusters_need_many_rounds():
+    # almost all points in two tight clusters: most rows overflow their hash value and take several rounds
+    rng = np.random.default_rng(42)
+    n = 4096
+    c = (rng.normal(size=(n, 3)) * 0.01).astype(np.float32)
+    c[::2] += 5.0
+    c[:50] = rng.random((50, 3)).astype(np.float32) * 10
+    feat = wl.f32_to_bf16_bits(rng.standard_normal((n, 16)).astype(np.float32))
+    ref = check_pool(c, None, feat, None, 1024, 2, 0.5, "zorder_div", "mean")
+    assert ref["step_of"].max() >= 6
+    check_pool(c, None, feat, None, 1024, 4, 0.5, "xor_div", "sum")
+
+
+def test_pool_empty_input_and_bad_offsets():
+    z = np.zeros((0, 3), np.float32)
+    got = f3d.inbucket_pool(dev(z), None, dev(np.zeros((0, 8), np.uint16), torch.bfloat16), None, 1024, 2, 0.1)
+    torch.cuda.synchronize()
+    assert got.pooled_offsets.cpu().numpy().tolist() == [0, 0]
+    rng = np.random.default_rng(43)
+    c = rng.random((1000, 3)).astype(np.float32)
+    feat = wl.f32_to_bf16_bits(rng.standard_normal((1000, 8)).astype(np.float32))
+    for bo in ([0, 600, 400, 1000], [0, 500, 900], [5, 500, 1000]):
+        got = f3d.inbucket_pool(dev(c), None, dev(feat, torch.bfloat16), dev(np.array(bo, dtype=np.int32)), 256, 2, 0.1)
+        torch.cuda.synchronize()
+        assert int(got.pooled_offsets[-1]) == -1
+
+
+def test_pool_after_attention_end_to_end():
+    # bucketize -> attention (bucket-major output) -> pooling of that output: the stage's three operators in a row
+    w = wl.make_workload("tiny")
+    bk, ref = check_bucketize(w.coords, w.batch_offsets, w.voxel_size, w.bucket_cap)
+    q, k, v = w.qkv()
+    out = f3d.bucket_swin_attn(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), bk, w.heads, w.head_dim, "plain")
+    torch.cuda.synchronize()
+    feat_bits = out.view(torch.int16).cpu().numpy().view(np.uint16)
+    check_pool(w.coords, ref["perm"], feat_bits, w.batch_offsets, 128, 2, 0.1, "zorder_div", "mean")
