@@ -117,6 +117,8 @@ def main() -> int:
                     help="query rows the oracle computes per pass (-1 = about 20 s of host work, 0 = skip)")
     ap.add_argument("--separate-unpermute", dest="fuse_unpermute", action="store_false",
                     help="run f3d_unpermute as a kernel of its own instead of folding it into the last pass's store")
+    ap.add_argument("--pool", type=int, default=0, metavar="RHO",
+                    help="also time f3d_inbucket_pool (mean, tiles of 1024 rows, this reduction factor) on the attention output")
     ap.add_argument("--ceilings", action="store_true",
                     help="also run the register-only issue-rate microbenchmark (MFMA only, softmax only, the attention "
                          "tile loop) and add its rates to the JSON line")
@@ -243,6 +245,24 @@ def main() -> int:
                       "placed_share": {"direct": float(placed[0]) / n, "probes": float(placed[1:7].sum()) / n,
                                        "recycle": float(placed[7]) / n}},
     }
+    if args.pool > 0:   # the stage's third operator, outside the headline step
+        rho = args.pool
+        pooled = f3d.inbucket_pool(coords, bk.perm, out, bo, 1024, rho, 0.1, args.hash, "mean")
+        pws = torch.empty(1 << 20, dtype=torch.uint8, device=dev)
+        torch.cuda.synchronize()
+        n_out = int(pooled.pooled_offsets[-1])
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            f3d.inbucket_pool(coords, bk.perm, out, bo, 1024, rho, 0.1, args.hash, "mean", pws, pooled)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        nbytes = n * (2 * C + 12 + 4 + 4) + n_out * (2 * C + 12)   # features, coordinates, perm, sub_of; pooled rows and positions
+        gbps = nbytes / (ms * 1e-3) / 1e9
+        res["pool"] = {"rho": rho, "tile": 1024, "op": "mean", "pooled_rows": n_out, "ms": ms, "points_per_s": n / (ms * 1e-3),
+                       "roofline": {"bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                    "frac": gbps / PEAK_HBM_GBPS, "bytes": nbytes}}
     if args.ceilings:
         res["ceilings"] = measured_ceilings(d)
     cpu_rows = args.cpu_rows

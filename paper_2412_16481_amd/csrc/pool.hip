@@ -139,7 +139,7 @@ __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w 
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
 // dynamic LDS, kp = a.kp: px,py,pz [PT] floats | ox,oy,oz [kp] floats | fill [kp] ints | wcnt [PW][kp] u16 |
-// open_list, id_of_hash, first_idx, ktot [kp] u16 each | members [PT + POOL_MAX_RHO] u16
+// open_list, id_of_hash, first_idx, ktot [kp] u16 each | members [PT + POOL_MAX_RHO] u16 | pick, rsub, rslot [PT] u16
 __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -166,6 +166,9 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
     uint16_t* first_idx = id_of_hash + kp;
     uint16_t* ktot = first_idx + kp;
     uint16_t* members = ktot + kp;
+    uint16_t* pick = members + PT + POOL_MAX_RHO;   // [PT] choice of the t-th row left
+    uint16_t* rsub = pick + PT;                      // [PT] sub-bucket it joined (0xFFFF: none yet) and its slot
+    uint16_t* rslot = rsub + PT;
 
     // ---- the tile's points, its minimum, voxel coordinates, voxel box
     const bool act = tid < n;
@@ -249,39 +252,145 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
     }
     bool left = act && sub < 0;
     // ---- rounds: every row still left picks the open sub-bucket whose first row is nearest (state at the start of
-    //      the round); the contenders of a sub-bucket join in row order while it has room
+    //      the round); the contenders of a sub-bucket join in row order while it has room. While many rows are
+    //      left the whole workgroup takes the round (a row per thread). The long tail of rounds with at most 64
+    //      rows left is run by wave 0 alone, without workgroup barriers: its lanes hold the rows in row order.
+    int lpos = 0, nleft = 0, nopen = 0;
+    uint16_t* left_list = members;   // [PT] thread ids of the rows still left, in row order (members is filled last)
     for (int round = 0; round <= PT; ++round) {   // every round places at least one row; the bound is a safeguard
-        if (!__syncthreads_or(left ? 1 : 0)) break;
+        // one scan builds both lists: the rows still left (low half) and the sub-buckets with room (high half)
+        __syncthreads();   // the fill levels written by the steps above / the last round are in place
         const bool open = tid < M && fill[tid] < rho;
-        int nopen;
-        const int pos = block_excl_scan(open ? 1 : 0, &nopen, lds);
+        int tot;
+        const int pre = block_excl_scan((left ? 1 : 0) | (open ? 0x10000 : 0), &tot, lds);
+        lpos = pre & 0xFFFF;
+        nleft = tot & 0xFFFF;
+        nopen = tot >> 16;
+        if (left) left_list[lpos] = (uint16_t)tid;
         if (open) {
-            const int f = first_idx[tid];
-            open_list[pos] = (uint16_t)tid;
-            ox[pos] = px[f];
-            oy[pos] = py[f];
-            oz[pos] = pz[f];
+            const int f = first_idx[tid], opos = pre >> 16;
+            open_list[opos] = (uint16_t)tid;
+            ox[opos] = px[f];
+            oy[opos] = py[f];
+            oz[opos] = pz[f];
         }
         __syncthreads();
-        int best = 0, bj = -1;
-        if (left) {
-            float bd = 0.f;
-            for (int j = 0; j < nopen; ++j) {   // ascending sub-bucket id: a tie keeps the lower id
-                const float dx = __fsub_rn(x, ox[j]), dy = __fsub_rn(y, oy[j]), dz = __fsub_rn(z, oz[j]);
+        if (nleft <= 64) break;
+        // the rows left are spread over all threads again: g neighbouring lanes share one row's search
+        int g = 1;
+        while (g < 64 && nleft * g * 2 <= PT) g *= 2;
+        const int p = tid / g, part = tid - p * g;
+        float bd = __builtin_inff();
+        int bi = 0x7FFFFFFF;
+        if (p < nleft) {
+            const int id = left_list[p];
+            const float qx = px[id], qy = py[id], qz = pz[id];
+            for (int c = part; c < nopen; c += g) {   // ascending: a tie keeps the lower sub-bucket id
+                const float dx = __fsub_rn(qx, ox[c]), dy = __fsub_rn(qy, oy[c]), dz = __fsub_rn(qz, oz[c]);
                 const float d2 = __fadd_rn(__fadd_rn(__fmul_rn(dx, dx), __fmul_rn(dy, dy)), __fmul_rn(dz, dz));
-                if (bj < 0 || d2 < bd) { bd = d2; bj = j; }
+                if (bi == 0x7FFFFFFF || d2 < bd) { bd = d2; bi = c; }
             }
-            if (bj >= 0) best = open_list[bj];
         }
-        const int rank = block_rank_by_key(best, left, keybits, M, wcnt, kp, nullptr);
-        const bool join = left && bj >= 0 && fill[best] + rank < rho;
-        if (join) {
-            sub = best;
-            slot = fill[best] + rank;
+        for (int d = g >> 1; d >= 1; d >>= 1) {   // smallest distance, the lower list position on a tie
+            const float od = __shfl_xor(bd, d, 64);
+            const int oi = __shfl_xor(bi, d, 64);
+            if (oi != 0x7FFFFFFF && (bi == 0x7FFFFFFF || od < bd || (od == bd && oi < bi))) { bd = od; bi = oi; }
         }
-        __syncthreads();   // every fill level has been read
+        if (p < nleft && part == 0) pick[p] = open_list[min(bi, nopen - 1)];
+        __syncthreads();
+        const bool dense = tid < nleft;   // thread t now speaks for the t-th row left: row order is kept
+        const int best = dense ? (int)pick[tid] : 0;
+        const int rank = block_rank_by_key(best, dense, keybits, M, wcnt, kp, nullptr);
+        const bool join = dense && fill[best] + rank < rho;
+        if (dense) {
+            rsub[tid] = join ? (uint16_t)best : (uint16_t)0xFFFF;
+            rslot[tid] = (uint16_t)(fill[best] + rank);
+        }
+        __syncthreads();   // every fill level has been read, every answer is written
         if (join) atomicAdd(&fill[best], 1);
-        left = left && !join;
+        if (left && rsub[lpos] != 0xFFFF) {
+            sub = rsub[lpos];
+            slot = rslot[lpos];
+            left = false;
+        }
+    }
+    if (nleft > 0 && nleft <= 64) {
+        // wave 0 takes the rows that are left (left_list, in row order) and the open list of this moment
+        uint16_t* tail_id = left_list;
+        uint16_t* res_sub = rsub;
+        uint16_t* res_slot = rslot;
+        if (tid < 64) {
+            const int L = nleft;
+            bool tl = lane < L;
+            const int me = tl ? (int)tail_id[lane] : 0;
+            const float qx0 = px[me], qy0 = py[me], qz0 = pz[me];
+            const unsigned long long lt = (1ull << lane) - 1ull;
+            int tsub = 0, tslot = 0, O = nopen;
+            for (int round = 0; round <= 64 && O > 0; ++round) {
+                const unsigned long long leftmask = __ballot(tl);
+                if (leftmask == 0ull) break;
+                // drop the sub-buckets that filled up (in place: a chunk is read before anything of it is overwritten)
+                int newO = 0;
+                for (int base = 0; base < O; base += 64) {
+                    const int c = base + lane;
+                    int s = 0;
+                    float cx = 0.f, cy = 0.f, cz = 0.f;
+                    bool keep = false;
+                    if (c < O) {
+                        s = open_list[c];
+                        cx = ox[c];
+                        cy = oy[c];
+                        cz = oz[c];
+                        keep = fill[s] < rho;
+                    }
+                    const unsigned long long bal = __ballot(keep);
+                    if (keep) {
+                        const int p = newO + __popcll(bal & lt);
+                        open_list[p] = (uint16_t)s;
+                        ox[p] = cx;
+                        oy[p] = cy;
+                        oz[p] = cz;
+                    }
+                    newO += __popcll(bal);
+                }
+                O = newO;
+                __threadfence_block();
+                if (O == 0) break;
+                // nearest open sub-bucket of this lane's row (ascending id: a tie keeps the lower one)
+                int mybest = 0;
+                if (tl) {
+                    float bd = 0.f;
+                    int bj = -1;
+                    for (int c = 0; c < O; ++c) {
+                        const float dx = __fsub_rn(qx0, ox[c]), dy = __fsub_rn(qy0, oy[c]), dz = __fsub_rn(qz0, oz[c]);
+                        const float d2 = __fadd_rn(__fadd_rn(__fmul_rn(dx, dx), __fmul_rn(dy, dy)), __fmul_rn(dz, dz));
+                        if (bj < 0 || d2 < bd) { bd = d2; bj = c; }
+                    }
+                    mybest = open_list[bj];
+                }
+                const unsigned long long m = match_key(mybest, tl, keybits);
+                const int rank = __popcll(m & lt);
+                const int room = tl ? rho - fill[mybest] : 0;
+                const bool join = tl && rank < room;
+                if (join) {
+                    tsub = mybest;
+                    tslot = fill[mybest] + rank;
+                }
+                __threadfence_block();   // every lane has read the fill levels
+                if (tl && rank == 0) fill[mybest] += min((int)__popcll(m), room);
+                __threadfence_block();
+                tl = tl && !join;
+            }
+            if (lane < L) {
+                res_sub[lane] = (uint16_t)tsub;
+                res_slot[lane] = (uint16_t)tslot;
+            }
+        }
+        __syncthreads();
+        if (left) {
+            sub = res_sub[lpos];
+            slot = res_slot[lpos];
+        }
     }
 
     // ---- members of every sub-bucket by slot, the map row -> pooled row
@@ -354,7 +463,7 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
 size_t pool_lds_bytes(int kp)
 {
     return (size_t)3 * PT * 4 + (size_t)3 * kp * 4 + (size_t)kp * 4 + (size_t)PW * kp * 2 + (size_t)4 * kp * 2 +
-           (size_t)(PT + POOL_MAX_RHO) * 2;
+           (size_t)(PT + POOL_MAX_RHO) * 2 + (size_t)3 * PT * 2;
 }
 
 }  // namespace
