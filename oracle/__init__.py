@@ -47,6 +47,7 @@ def lib() -> ctypes.CDLL:
         _lib.orc_unpermute.restype = ctypes.c_int
         _lib.orc_max_threads.restype = ctypes.c_int
         _lib.orc_pool_assign.restype = ctypes.c_int64
+        _lib.orc_attn_bwd.restype = ctypes.c_int64
         _lib.orc_pool_reduce.restype = ctypes.c_int
     return _lib
 
@@ -118,6 +119,31 @@ def attn(q: np.ndarray, k: np.ndarray, v: np.ndarray, perm: Optional[np.ndarray]
                        _p(sel), _p(out))
     if r < 0:
         raise ValueError("orc_attn: bad arguments")
+    return out
+
+
+def attn_bwd(q: np.ndarray, k: np.ndarray, v: np.ndarray, dout: np.ndarray, perm: Optional[np.ndarray], offsets: np.ndarray,
+             scan_bucket_start: np.ndarray, scope_buckets: int, mode: str, heads: int, head_dim: int, shift: int = 2,
+             stride: int = 2, scale: Optional[float] = None, scope_sel: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+    """Gradient of the scope-restricted attention in binary64. q,k,v,dout: uint16 bf16 bit patterns
+    [n, heads*head_dim]; dout belongs to the bucket-major output rows. Returns dq, dk, dv [n, C] (bucket-major
+    rows), lse [n, heads] (natural log) and done [n] (1 where the row's scope was computed)."""
+    q, k, v, dout = (np.ascontiguousarray(a, dtype=np.uint16) for a in (q, k, v, dout))
+    n, C = q.shape
+    off = np.ascontiguousarray(offsets, dtype=np.int32)
+    sbs = np.ascontiguousarray(scan_bucket_start, dtype=np.int32)
+    pm = None if perm is None else np.ascontiguousarray(perm, dtype=np.int32)
+    sel = None if scope_sel is None else np.ascontiguousarray(scope_sel, dtype=np.uint8)
+    out = {name: np.full((n, C), np.nan, dtype=np.float64) for name in ("dq", "dk", "dv")}
+    out["lse"] = np.full((n, heads), np.nan, dtype=np.float64)
+    out["done"] = np.zeros(n, dtype=np.uint8)
+    sc = (1.0 / np.sqrt(float(head_dim))) if scale is None else float(scale)
+    r = lib().orc_attn_bwd(_p(q), _p(k), _p(v), _p(dout), _p(pm), _p(off), _p(sbs), ctypes.c_int32(sbs.shape[0] - 1),
+                           ctypes.c_int32(scope_buckets), ctypes.c_int32(MODES[mode]), ctypes.c_int32(shift),
+                           ctypes.c_int32(stride), ctypes.c_int32(heads), ctypes.c_int32(head_dim), ctypes.c_double(sc),
+                           _p(sel), _p(out["dq"]), _p(out["dk"]), _p(out["dv"]), _p(out["lse"]), _p(out["done"]))
+    if r < 0:
+        raise ValueError("orc_attn_bwd: bad arguments")
     return out
 
 

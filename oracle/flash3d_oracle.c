@@ -11,6 +11,7 @@
  *   - scatter index bucket_base[bucket_id] + bucket_off  (Section 4.1, "Input and Output")
  *   - scope regrouping: plain / shifted / strided        (Section 4.2, worked example; Table 2 caption)
  *   - multi-head self-attention inside one scope         (Section 4.2; Appendix "Bucket-Swin")
+ *   - gradient of that attention (plain definition)       (Section 4.2; the experiments report training latency)
  *   - in-bucket pooling: sub-bucket construction, reduce  (Section 4.2 "In-bucket Pooling"; Appendix "In-bucket Pooling")
  *
  * Algorithms 1 and 2 let hardware atomics decide the arrival order, so their result depends on
@@ -358,6 +359,120 @@ int64_t orc_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, const 
                 }
             }
             free(sc);
+            free(rows);
+        }
+    }
+    return visited;
+}
+
+/*
+ * Gradient of the scope-restricted attention above (what training needs; the paper reports training
+ * latency in its experiments). Plain definition, binary64, scope by scope and head by head:
+ *   S = scale * Q K^T,  P = softmax_rows(S),  O = P V,
+ *   dV = P^T dO,  dP = dO V^T,  D_i = sum_j P_ij dP_ij,  dS = P o (dP - D),  dQ = scale * dS K,  dK = scale * dS^T Q.
+ * q,k,v: bf16 [n,C] read through perm as in orc_attn; dout: bf16 [n,C] gradient of the BUCKET-MAJOR output rows.
+ * dq, dk, dv: binary64 [n,C], BUCKET-MAJOR rows (row p = gradient of the input row stored at p). lse (may be NULL):
+ * [n, heads] natural-log sum of exponentials of the scaled scores of row p. scope_sel (may be NULL): [n] flags;
+ * only the scopes that contain a flagged row are computed, and done[p] (may be NULL) is set to 1 for their rows.
+ * returns the number of scopes computed, -1 on bad arguments.
+ */
+int64_t orc_attn_bwd(const uint16_t *q, const uint16_t *k, const uint16_t *v, const uint16_t *dout, const int32_t *perm,
+                     const int32_t *offsets, const int32_t *scan_bucket_start, int32_t n_scans, int32_t m, int32_t mode,
+                     int32_t s, int32_t t, int32_t heads, int32_t head_dim, double scale, const uint8_t *scope_sel,
+                     double *dq, double *dk, double *dv, double *lse, uint8_t *done)
+{
+    if (m <= 0 || heads <= 0 || head_dim <= 0 || mode < 0 || mode > 2) return -1;
+    if (mode == ORC_SHIFT && (s <= 0 || s >= m)) return -1;
+    if (mode == ORC_STRIDE && t <= 0) return -1;
+    const int64_t C = (int64_t)heads * head_dim;
+    int64_t visited = 0;
+    for (int32_t b = 0; b < n_scans; ++b) {
+        const int64_t kb0 = scan_bucket_start[b], K = scan_bucket_start[b + 1] - kb0;
+        if (K <= 0) continue;
+        int64_t ngroups = 0;
+        for (int64_t j = 0; j < K; ++j) {
+            int64_t g = orc_group_of_bucket(j, m, mode, s, t);
+            if (g + 1 > ngroups) ngroups = g + 1;
+        }
+#pragma omp parallel for schedule(dynamic, 1) reduction(+ : visited)
+        for (int64_t g = 0; g < ngroups; ++g) {
+            int64_t ng = 0;
+            for (int64_t j = 0; j < K; ++j)
+                if (orc_group_of_bucket(j, m, mode, s, t) == g) ng += offsets[kb0 + j + 1] - offsets[kb0 + j];
+            if (ng == 0) continue;
+            int64_t *rows = (int64_t *)malloc(sizeof(int64_t) * (size_t)ng);
+            int64_t c = 0;
+            int wanted = scope_sel ? 0 : 1;
+            for (int64_t j = 0; j < K; ++j)
+                if (orc_group_of_bucket(j, m, mode, s, t) == g)
+                    for (int64_t p = offsets[kb0 + j]; p < offsets[kb0 + j + 1]; ++p) {
+                        rows[c++] = p;
+                        if (scope_sel && scope_sel[p]) wanted = 1;
+                    }
+            if (!wanted) { free(rows); continue; }
+            ++visited;
+            double *P = (double *)malloc(sizeof(double) * (size_t)ng * (size_t)ng);
+            double *dS = (double *)malloc(sizeof(double) * (size_t)ng * (size_t)ng);
+            for (int32_t h = 0; h < heads; ++h) {
+                const int64_t co = (int64_t)h * head_dim;
+                for (int64_t a = 0; a < ng; ++a) {          /* P = softmax(scale Q K^T), row by row */
+                    const int64_t ia = perm ? perm[rows[a]] : rows[a];
+                    double mx = -INFINITY;
+                    for (int64_t bb = 0; bb < ng; ++bb) {
+                        const int64_t ib = perm ? perm[rows[bb]] : rows[bb];
+                        double dot = 0.0;
+                        for (int32_t e = 0; e < head_dim; ++e)
+                            dot += bf16_to_double(q[ia * C + co + e]) * bf16_to_double(k[ib * C + co + e]);
+                        P[a * ng + bb] = dot * scale;
+                        if (P[a * ng + bb] > mx) mx = P[a * ng + bb];
+                    }
+                    double den = 0.0;
+                    for (int64_t bb = 0; bb < ng; ++bb) {
+                        P[a * ng + bb] = exp(P[a * ng + bb] - mx);
+                        den += P[a * ng + bb];
+                    }
+                    for (int64_t bb = 0; bb < ng; ++bb) P[a * ng + bb] /= den;
+                    if (lse) lse[rows[a] * heads + h] = mx + log(den);
+                }
+                for (int64_t a = 0; a < ng; ++a) {          /* dP = dO V^T, D, dS */
+                    double D = 0.0;
+                    for (int64_t bb = 0; bb < ng; ++bb) {
+                        const int64_t ib = perm ? perm[rows[bb]] : rows[bb];
+                        double dp = 0.0;
+                        for (int32_t e = 0; e < head_dim; ++e)
+                            dp += bf16_to_double(dout[rows[a] * C + co + e]) * bf16_to_double(v[ib * C + co + e]);
+                        dS[a * ng + bb] = dp;
+                        D += P[a * ng + bb] * dp;
+                    }
+                    for (int64_t bb = 0; bb < ng; ++bb) dS[a * ng + bb] = P[a * ng + bb] * (dS[a * ng + bb] - D);
+                }
+                for (int64_t a = 0; a < ng; ++a) {          /* dQ = scale dS K */
+                    for (int32_t e = 0; e < head_dim; ++e) {
+                        double acc = 0.0;
+                        for (int64_t bb = 0; bb < ng; ++bb) {
+                            const int64_t ib = perm ? perm[rows[bb]] : rows[bb];
+                            acc += dS[a * ng + bb] * bf16_to_double(k[ib * C + co + e]);
+                        }
+                        dq[rows[a] * C + co + e] = scale * acc;
+                    }
+                }
+                for (int64_t bb = 0; bb < ng; ++bb) {       /* dK = scale dS^T Q,  dV = P^T dO */
+                    for (int32_t e = 0; e < head_dim; ++e) {
+                        double acck = 0.0, accv = 0.0;
+                        for (int64_t a = 0; a < ng; ++a) {
+                            const int64_t ia = perm ? perm[rows[a]] : rows[a];
+                            acck += dS[a * ng + bb] * bf16_to_double(q[ia * C + co + e]);
+                            accv += P[a * ng + bb] * bf16_to_double(dout[rows[a] * C + co + e]);
+                        }
+                        dk[rows[bb] * C + co + e] = scale * acck;
+                        dv[rows[bb] * C + co + e] = accv;
+                    }
+                }
+            }
+            if (done)
+                for (int64_t a = 0; a < ng; ++a) done[rows[a]] = 1;
+            free(dS);
+            free(P);
             free(rows);
         }
     }
