@@ -147,12 +147,15 @@ static inline int f3d_psh_bucketize_simple(const float *coords, int64_t n, float
  *   out_perm    NULL, or [n] int32, a permutation: the result for bucket-major row p is stored at row
  *               out_perm[p] instead. Passing `perm` returns the last layer's output in the input order of the
  *               points, i.e. f3d_unpermute folded into the store (4-byte aligned; must not alias q, k, v)
+ *   lse  (out)  NULL, or binary32 [n, heads], BUCKET-MAJOR rows (out_perm does not apply): natural logarithm of
+ *               the sum of exponentials of the row's scaled scores; what f3d_bucket_swin_attn_bwd needs
  * Arithmetic: bf16 operands, fp32 accumulation and softmax, probabilities rounded to bf16 before P*V.
  */
 int f3d_bucket_swin_attn(const void *q, const void *k, const void *v, const int32_t *perm, const int32_t *offsets,
                          const int32_t *scan_bucket_start, int64_t n, int32_t n_scans, int64_t max_buckets,
                          int32_t bucket_cap, int32_t scope_buckets, int32_t mode, int32_t shift, int32_t stride, int32_t heads,
-                         int32_t head_dim, float softmax_scale, void *out, const int32_t *out_perm, void *stream);
+                         int32_t head_dim, float softmax_scale, void *out, const int32_t *out_perm, float *lse,
+                         void *stream);
 
 /*
  * In-bucket pooling (Section 4.2 "In-bucket Pooling"; Appendix "In-bucket Pooling"): the bucket-major array is

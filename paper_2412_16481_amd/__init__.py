@@ -65,7 +65,7 @@ def lib() -> ctypes.CDLL:
         L.f3d_psh_bucketize.argtypes = [vp, vp, i64, i32, ctypes.POINTER(f3d_params), vp, vp, vp, vp, vp, vp,
                                         ctypes.c_size_t, vp]
         L.f3d_psh_bucketize.restype = ctypes.c_int
-        L.f3d_bucket_swin_attn.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, i32, i32, i32, i32, i32, i32, f32, vp, vp, vp]
+        L.f3d_bucket_swin_attn.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, i32, i32, i32, i32, i32, i32, f32, vp, vp, vp, vp]
         L.f3d_bucket_swin_attn.restype = ctypes.c_int
         L.f3d_pool_max_rows.argtypes = [i64, i32, i32, i32]
         L.f3d_pool_max_rows.restype = i64
@@ -172,10 +172,12 @@ def psh_bucketize(coords, batch_offsets, params: f3d_params, workspace=None, out
 
 
 def bucket_swin_attn(q, k, v, buckets: Buckets, heads: int, head_dim: int, mode: str = "plain", shift: int = 2,
-                     stride: int = 2, use_perm: bool = True, softmax_scale: float = 0.0, out=None, original_order: bool = False):
+                     stride: int = 2, use_perm: bool = True, softmax_scale: float = 0.0, out=None, original_order: bool = False,
+                     lse=None):
     """f3d_bucket_swin_attn. q,k,v: bfloat16 [n, heads*head_dim]; rows in input order when use_perm, else
     already bucket-major. Returns bfloat16 [n, heads*head_dim] in bucket-major row order, or, with
-    original_order, in the input order of the points (the unpermute folded into the kernel's store)."""
+    original_order, in the input order of the points (the unpermute folded into the kernel's store). lse: optional
+    float32 [n, heads] tensor that receives the rows' log-sum-exp (bucket-major), for the backward pass."""
     import torch
     for t in (q, k, v):
         assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.shape == (buckets.n, heads * head_dim)
@@ -185,7 +187,7 @@ def bucket_swin_attn(q, k, v, buckets: Buckets, heads: int, head_dim: int, mode:
                                     _ptr(buckets.offsets), _ptr(buckets.scan_bucket_start), buckets.n, buckets.n_scans,
                                     buckets.max_buckets, buckets.bucket_cap, buckets.scope_buckets, MODES[mode] if isinstance(mode, str) else mode,
                                     shift, stride, heads, head_dim, softmax_scale, _ptr(out),
-                                    _ptr(buckets.perm) if original_order else None, _stream())
+                                    _ptr(buckets.perm) if original_order else None, _ptr(lse), _stream())
     if rc != F3D_OK:
         raise Flash3DError(rc, "f3d_bucket_swin_attn")
     return out

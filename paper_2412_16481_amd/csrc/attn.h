@@ -10,6 +10,7 @@ struct AttnArgs {
     const uint16_t* k;
     const uint16_t* v;
     uint16_t* out;
+    float* lse;                // null, or [n, H]: natural-log sum of exponentials of every row's scaled scores (bucket-major)
     const int32_t* out_perm;   // null: out is bucket-major; else the result of bucket-major row p goes to row out_perm[p]
     const int32_t* perm;     // may be null
     const int32_t* offsets;

@@ -209,7 +209,7 @@ int f3d_psh_bucketize(const float* coords, const int32_t* batch_offsets, int64_t
 int f3d_bucket_swin_attn(const void* q, const void* k, const void* v, const int32_t* perm, const int32_t* offsets,
                          const int32_t* scan_bucket_start, int64_t n, int32_t n_scans, int64_t max_buckets,
                          int32_t bucket_cap, int32_t scope_buckets, int32_t mode, int32_t shift, int32_t stride, int32_t heads,
-                         int32_t head_dim, float softmax_scale, void* out, const int32_t* out_perm, void* stream)
+                         int32_t head_dim, float softmax_scale, void* out, const int32_t* out_perm, float* lse, void* stream)
 {
     if (n < 0 || n_scans < 1 || heads < 1 || bucket_cap < 1 || scope_buckets < 1 || max_buckets < 0) return F3D_ERR_INVALID_ARG;
     if (mode < F3D_PLAIN || mode > F3D_STRIDE) return F3D_ERR_INVALID_ARG;
@@ -224,7 +224,7 @@ int f3d_bucket_swin_attn(const void* q, const void* k, const void* v, const int3
     if (n == 0) return F3D_OK;
     if (!q || !k || !v || !out) return F3D_ERR_INVALID_ARG;
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) return F3D_ERR_BAD_ALIGNMENT;
-    if ((uintptr_t)out_perm & 3) return F3D_ERR_BAD_ALIGNMENT;
+    if (((uintptr_t)out_perm | (uintptr_t)lse) & 3) return F3D_ERR_BAD_ALIGNMENT;
     if (((uintptr_t)perm | (uintptr_t)offsets | (uintptr_t)scan_bucket_start) & 3) return F3D_ERR_BAD_ALIGNMENT;
 
     f3d::AttnArgs a;
@@ -234,6 +234,7 @@ int f3d_bucket_swin_attn(const void* q, const void* k, const void* v, const int3
     a.v = (const uint16_t*)v;
     a.out = (uint16_t*)out;
     a.out_perm = out_perm;
+    a.lse = lse;
     a.perm = perm;
     a.offsets = offsets;
     a.sbs = scan_bucket_start;

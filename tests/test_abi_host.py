@@ -104,7 +104,7 @@ def test_attention_refuses_bad_arguments_on_the_host():
     def call(**o):
         return L.f3d_bucket_swin_attn(o.get("q", fake), fake, fake, None, o.get("offsets", fake), fake, o.get("n", 100), 1, 10,
                                       o.get("cap", 1024), o.get("m", 4), o.get("mode", 0), o.get("shift", 2),
-                                      o.get("stride", 2), o.get("heads", 4), o.get("d", 16), o.get("scale", 0.0), fake, o.get("out_perm"), None)
+                                      o.get("stride", 2), o.get("heads", 4), o.get("d", 16), o.get("scale", 0.0), fake, o.get("out_perm"), o.get("lse"), None)
     assert call(d=24) == f3d.ERR_UNSUPPORTED
     assert call(d=64) == f3d.ERR_UNSUPPORTED
     assert call(mode=3) == f3d.ERR_INVALID_ARG
@@ -116,6 +116,7 @@ def test_attention_refuses_bad_arguments_on_the_host():
     assert call(scale=-1.0) == f3d.ERR_INVALID_ARG
     assert call(q=None) == f3d.ERR_INVALID_ARG
     assert call(out_perm=fake + 2) == f3d.ERR_BAD_ALIGNMENT
+    assert call(lse=fake + 1) == f3d.ERR_BAD_ALIGNMENT
     assert call(q=fake + 2) == f3d.ERR_BAD_ALIGNMENT
     assert call(offsets=None) == f3d.ERR_INVALID_ARG
     assert call(n=-5) == f3d.ERR_INVALID_ARG

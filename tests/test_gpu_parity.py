@@ -299,6 +299,21 @@ def test_attention_closed_forms_on_gpu():
     assert np.abs(out.float().cpu().numpy() - want).max() <= 2.0 ** -7 * np.abs(want).max()
 
 
+def test_attention_log_sum_exp_output():
+    # natural-log sum of exponentials per row and head, bucket-major; also on scores large enough for the second sweep
+    for d, heads, scale_in in ((16, 2, 1.0), (32, 2, 1.0), (16, 2, 8.0)):
+        bk, ref, n = hand_layout([[64, 64, 37, 64, 1, 64, 64, 64, 50], [17]], 256, 4)
+        rng = np.random.default_rng(36)
+        q, k, v = (wl.f32_to_bf16_bits((rng.standard_normal((n, heads * d)) * s).astype(np.float32)) for s in (scale_in, scale_in, 1.0))
+        for mode in ("plain", "shift", "stride"):
+            lse = torch.empty(n, heads, dtype=torch.float32, device=DEV)
+            f3d.bucket_swin_attn(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), bk, heads, d, mode, lse=lse)
+            torch.cuda.synchronize()
+            want = oracle.attn_bwd(q, k, v, v, ref["perm"], ref["offsets"], ref["scan_bucket_start"], 4, mode, heads, d)["lse"]
+            # the denominator is a sum of probabilities rounded to bf16 (relative 2^-9 each): 4e-3 bounds the logarithm's error
+            assert np.abs(lse.cpu().numpy() - want).max() <= 4e-3
+
+
 # ----------------------------------------------------------------------------- unpermute, end to end
 
 
