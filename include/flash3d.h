@@ -158,6 +158,32 @@ int f3d_bucket_swin_attn(const void *q, const void *k, const void *v, const int3
                          void *stream);
 
 /*
+ * Backward of f3d_bucket_swin_attn (Section 4.2; the experiments report training latency): given the gradient dout of
+ * the BUCKET-MAJOR output rows, the gradients of q, k and v inside every scope,
+ *   P = exp(scale q k^T - lse),  dP = dout v^T,  D = rowsum(dout o out),  dS = P o (dP - D),
+ *   dq = scale dS k,  dk = scale dS^T q,  dv = P^T dout.
+ *
+ *   q, k, v, perm, offsets, scan_bucket_start, n .. softmax_scale   exactly as in the forward call
+ *   out         bf16 [n, heads*head_dim], the forward output, bucket-major (not written with out_perm)
+ *   dout        bf16 [n, heads*head_dim], bucket-major
+ *   lse         binary32 [n, heads], the forward call's lse output
+ *   dq, dk, dv (out)  bf16 [n, heads*head_dim]: row p holds the gradient of the q/k/v row that bucket-major row p
+ *               was read from; with grad_perm it is stored at row grad_perm[p] instead (passing perm returns the
+ *               gradients in the input order of the points)
+ *   grad_perm   NULL or [n] int32, a permutation
+ *   workspace   >= f3d_attn_bwd_workspace_bytes(n, heads), 256-byte aligned
+ * Arithmetic: bf16 operands, fp32 accumulation; P and dS are rounded to bf16 before the second products.
+ */
+int f3d_attn_bwd_workspace_bytes(int64_t n, int32_t heads, size_t *out_bytes);
+
+int f3d_bucket_swin_attn_bwd(const void *q, const void *k, const void *v, const void *out, const void *dout,
+                             const float *lse, const int32_t *perm, const int32_t *offsets,
+                             const int32_t *scan_bucket_start, int64_t n, int32_t n_scans, int64_t max_buckets,
+                             int32_t bucket_cap, int32_t scope_buckets, int32_t mode, int32_t shift, int32_t stride,
+                             int32_t heads, int32_t head_dim, float softmax_scale, void *dq, void *dk, void *dv,
+                             const int32_t *grad_perm, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * In-bucket pooling (Section 4.2 "In-bucket Pooling"; Appendix "In-bucket Pooling"): the bucket-major array is
  * cut into tiles of `tile` consecutive rows (tiles start at a scan's first row and never span scans); inside a
  * tile of n rows, M = ceil(n / rho) sub-buckets of capacity rho are built in the Appendix's three steps (initial

@@ -21,7 +21,7 @@ MODES = {"plain": 0, "shift": 1, "stride": 2}
 SCHEDULES = {"auto": 0, "general": 1, "steps": 2}
 
 EXPORTS = ("f3d_params_default", "f3d_max_buckets", "f3d_workspace_bytes", "f3d_psh_bucketize",
-           "f3d_bucket_swin_attn", "f3d_pool_max_rows", "f3d_pool_workspace_bytes", "f3d_inbucket_pool",
+           "f3d_bucket_swin_attn", "f3d_attn_bwd_workspace_bytes", "f3d_bucket_swin_attn_bwd", "f3d_pool_max_rows", "f3d_pool_workspace_bytes", "f3d_inbucket_pool",
            "f3d_unpermute", "f3d_error_string", "f3d_last_hip_error", "f3d_version")
 POOL_OPS = {"sum": 0, "mean": 1, "min": 2, "max": 3}
 
@@ -67,6 +67,11 @@ def lib() -> ctypes.CDLL:
         L.f3d_psh_bucketize.restype = ctypes.c_int
         L.f3d_bucket_swin_attn.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, i32, i32, i32, i32, i32, i32, f32, vp, vp, vp, vp]
         L.f3d_bucket_swin_attn.restype = ctypes.c_int
+        L.f3d_attn_bwd_workspace_bytes.argtypes = [i64, i32, ctypes.POINTER(ctypes.c_size_t)]
+        L.f3d_attn_bwd_workspace_bytes.restype = ctypes.c_int
+        L.f3d_bucket_swin_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, i32, i32, i32, i32, i32, i32, f32,
+                                               vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.f3d_bucket_swin_attn_bwd.restype = ctypes.c_int
         L.f3d_pool_max_rows.argtypes = [i64, i32, i32, i32]
         L.f3d_pool_max_rows.restype = i64
         L.f3d_pool_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(ctypes.c_size_t)]
@@ -191,6 +196,32 @@ def bucket_swin_attn(q, k, v, buckets: Buckets, heads: int, head_dim: int, mode:
     if rc != F3D_OK:
         raise Flash3DError(rc, "f3d_bucket_swin_attn")
     return out
+
+
+def bucket_swin_attn_bwd(q, k, v, out, dout, lse, buckets: Buckets, heads: int, head_dim: int, mode: str = "plain",
+                         shift: int = 2, stride: int = 2, use_perm: bool = True, softmax_scale: float = 0.0,
+                         original_order: bool = False, workspace=None):
+    """f3d_bucket_swin_attn_bwd. out, dout: bfloat16 [n, C] bucket-major; lse: float32 [n, heads] from the forward
+    call. Returns (dq, dk, dv), bfloat16 [n, C], bucket-major rows or, with original_order, input order."""
+    import torch
+    n = buckets.n
+    for t in (q, k, v, out, dout):
+        assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.shape == (n, heads * head_dim)
+    assert lse.is_cuda and lse.dtype == torch.float32 and lse.is_contiguous() and lse.shape == (n, heads)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    if workspace is None:
+        nb = ctypes.c_size_t(0)
+        lib().f3d_attn_bwd_workspace_bytes(n, heads, ctypes.byref(nb))
+        workspace = torch.empty(max(int(nb.value), 256), dtype=torch.uint8, device=q.device)
+    rc = lib().f3d_bucket_swin_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(dout), _ptr(lse),
+                                        _ptr(buckets.perm) if use_perm else None, _ptr(buckets.offsets),
+                                        _ptr(buckets.scan_bucket_start), n, buckets.n_scans, buckets.max_buckets,
+                                        buckets.bucket_cap, buckets.scope_buckets, MODES[mode] if isinstance(mode, str) else mode,
+                                        shift, stride, heads, head_dim, softmax_scale, _ptr(dq), _ptr(dk), _ptr(dv),
+                                        _ptr(buckets.perm) if original_order else None, _ptr(workspace), workspace.numel(), _stream())
+    if rc != F3D_OK:
+        raise Flash3DError(rc, "f3d_bucket_swin_attn_bwd")
+    return dq, dk, dv
 
 
 @dataclass

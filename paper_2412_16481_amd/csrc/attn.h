@@ -29,6 +29,21 @@ struct AttnArgs {
     int extra;    // spare slots per scan: 2 (plain, shift) or stride + 1
 };
 
+// Backward pass: the forward arguments (f.out = the forward output O, f.lse = its log-sum-exp, f.out_perm = where a
+// gradient row goes, null = bucket-major) plus the incoming gradient and the three outgoing ones.
+struct AttnBwdArgs {
+    AttnArgs f;
+    const uint16_t* dout;   // bf16 [n, C], gradient of the bucket-major output rows
+    float* dsum;            // workspace [n, H]: sum over the head's channels of dO * O
+    uint16_t* dq;           // bf16 [n, C]
+    uint16_t* dk;
+    uint16_t* dv;
+    float scale;            // softmax scale (the forward's c_log2 divided by log2 e)
+    int kblocks;            // ceil(bucket_cap / 128): key blocks of a scope in the dK/dV kernel
+};
+
+hipError_t attn_bwd_launch(const AttnBwdArgs& a, int head_dim, hipStream_t stream);
+
 int attn_block_rows(int head_dim, long long slots, int heads, int bucket_cap);   // query rows one workgroup covers
 hipError_t attn_launch(const AttnArgs& a, int head_dim, int block_rows, hipStream_t stream);
 

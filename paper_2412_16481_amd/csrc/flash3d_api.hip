@@ -206,10 +206,11 @@ int f3d_psh_bucketize(const float* coords, const int32_t* batch_offsets, int64_t
     return e == hipSuccess ? F3D_OK : hip_fail(e);
 }
 
-int f3d_bucket_swin_attn(const void* q, const void* k, const void* v, const int32_t* perm, const int32_t* offsets,
-                         const int32_t* scan_bucket_start, int64_t n, int32_t n_scans, int64_t max_buckets,
-                         int32_t bucket_cap, int32_t scope_buckets, int32_t mode, int32_t shift, int32_t stride, int32_t heads,
-                         int32_t head_dim, float softmax_scale, void* out, const int32_t* out_perm, float* lse, void* stream)
+// argument checks and the launch geometry shared by the forward and backward attention calls
+static int fill_attn_args(f3d::AttnArgs& a, const void* q, const void* k, const void* v, const int32_t* perm, const int32_t* offsets,
+                          const int32_t* scan_bucket_start, int64_t n, int32_t n_scans, int64_t max_buckets, int32_t bucket_cap,
+                          int32_t scope_buckets, int32_t mode, int32_t shift, int32_t stride, int32_t heads, int32_t head_dim,
+                          float softmax_scale, float* scale_out, long long* slots_out)
 {
     if (n < 0 || n_scans < 1 || heads < 1 || bucket_cap < 1 || scope_buckets < 1 || max_buckets < 0) return F3D_ERR_INVALID_ARG;
     if (mode < F3D_PLAIN || mode > F3D_STRIDE) return F3D_ERR_INVALID_ARG;
@@ -221,20 +222,13 @@ int f3d_bucket_swin_attn(const void* q, const void* k, const void* v, const int3
     if (scope_buckets > F3D_MAX_SCOPE_BUCKETS || stride > 4096 || n_scans > 65535) return F3D_ERR_UNSUPPORTED;
     if (n >= (int64_t)2147483647 - (1 << 20) || (long long)heads * head_dim > 65536) return F3D_ERR_UNSUPPORTED;
     if (!offsets || !scan_bucket_start) return F3D_ERR_INVALID_ARG;
-    if (n == 0) return F3D_OK;
-    if (!q || !k || !v || !out) return F3D_ERR_INVALID_ARG;
-    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) return F3D_ERR_BAD_ALIGNMENT;
-    if (((uintptr_t)out_perm | (uintptr_t)lse) & 3) return F3D_ERR_BAD_ALIGNMENT;
+    if (n > 0 && (!q || !k || !v)) return F3D_ERR_INVALID_ARG;
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v) & 15) return F3D_ERR_BAD_ALIGNMENT;
     if (((uintptr_t)perm | (uintptr_t)offsets | (uintptr_t)scan_bucket_start) & 3) return F3D_ERR_BAD_ALIGNMENT;
-
-    f3d::AttnArgs a;
     memset(&a, 0, sizeof(a));
     a.q = (const uint16_t*)q;
     a.k = (const uint16_t*)k;
     a.v = (const uint16_t*)v;
-    a.out = (uint16_t*)out;
-    a.out_perm = out_perm;
-    a.lse = lse;
     a.perm = perm;
     a.offsets = offsets;
     a.sbs = scan_bucket_start;
@@ -249,13 +243,81 @@ int f3d_bucket_swin_attn(const void* q, const void* k, const void* v, const int3
     const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / sqrtf((float)head_dim);
     a.c_log2 = scale * 1.44269504088896340736f;
     a.extra = mode == F3D_STRIDE ? stride + 1 : 2;
-    const long long slots = max_buckets / scope_buckets + (long long)a.extra * n_scans + 1;
+    *scale_out = scale;
+    *slots_out = max_buckets / scope_buckets + (long long)a.extra * n_scans + 1;
+    return F3D_OK;
+}
+
+int f3d_bucket_swin_attn(const void* q, const void* k, const void* v, const int32_t* perm, const int32_t* offsets,
+                         const int32_t* scan_bucket_start, int64_t n, int32_t n_scans, int64_t max_buckets,
+                         int32_t bucket_cap, int32_t scope_buckets, int32_t mode, int32_t shift, int32_t stride, int32_t heads,
+                         int32_t head_dim, float softmax_scale, void* out, const int32_t* out_perm, float* lse, void* stream)
+{
+    f3d::AttnArgs a;
+    float scale;
+    long long slots;
+    const int rc = fill_attn_args(a, q, k, v, perm, offsets, scan_bucket_start, n, n_scans, max_buckets, bucket_cap, scope_buckets,
+                                  mode, shift, stride, heads, head_dim, softmax_scale, &scale, &slots);
+    if (rc != F3D_OK) return rc;
+    if (n == 0) return F3D_OK;
+    if (!out) return F3D_ERR_INVALID_ARG;
+    if ((uintptr_t)out & 15) return F3D_ERR_BAD_ALIGNMENT;
+    if (((uintptr_t)out_perm | (uintptr_t)lse) & 3) return F3D_ERR_BAD_ALIGNMENT;
+    a.out = (uint16_t*)out;
+    a.out_perm = out_perm;
+    a.lse = lse;
     const int bm = f3d::attn_block_rows(head_dim, slots, heads, bucket_cap);
     a.qblocks = (bucket_cap + bm - 1) / bm;
     if (slots * heads * a.qblocks > 2000000000ll) return F3D_ERR_UNSUPPORTED;
     a.n_slots = (int)slots;
     (void)hipGetLastError();
     const hipError_t e = f3d::attn_launch(a, head_dim, bm, (hipStream_t)stream);
+    return e == hipSuccess ? F3D_OK : hip_fail(e);
+}
+
+int f3d_attn_bwd_workspace_bytes(int64_t n, int32_t heads, size_t* out_bytes)
+{
+    if (!out_bytes || n < 0 || heads < 1) return F3D_ERR_INVALID_ARG;
+    *out_bytes = align_up((size_t)n * heads * sizeof(float), 256);
+    return F3D_OK;
+}
+
+int f3d_bucket_swin_attn_bwd(const void* q, const void* k, const void* v, const void* out, const void* dout, const float* lse,
+                             const int32_t* perm, const int32_t* offsets, const int32_t* scan_bucket_start, int64_t n,
+                             int32_t n_scans, int64_t max_buckets, int32_t bucket_cap, int32_t scope_buckets, int32_t mode,
+                             int32_t shift, int32_t stride, int32_t heads, int32_t head_dim, float softmax_scale, void* dq, void* dk,
+                             void* dv, const int32_t* grad_perm, void* workspace, size_t workspace_bytes, void* stream)
+{
+    f3d::AttnBwdArgs b;
+    memset(&b, 0, sizeof(b));
+    float scale;
+    long long slots;
+    const int rc = fill_attn_args(b.f, q, k, v, perm, offsets, scan_bucket_start, n, n_scans, max_buckets, bucket_cap, scope_buckets,
+                                  mode, shift, stride, heads, head_dim, softmax_scale, &scale, &slots);
+    if (rc != F3D_OK) return rc;
+    if (n == 0) return F3D_OK;
+    if (!out || !dout || !lse || !dq || !dk || !dv || !workspace) return F3D_ERR_INVALID_ARG;
+    if (((uintptr_t)out | (uintptr_t)dout | (uintptr_t)dq | (uintptr_t)dk | (uintptr_t)dv) & 15) return F3D_ERR_BAD_ALIGNMENT;
+    if (((uintptr_t)lse | (uintptr_t)grad_perm) & 3) return F3D_ERR_BAD_ALIGNMENT;
+    if ((uintptr_t)workspace & 255) return F3D_ERR_BAD_ALIGNMENT;
+    size_t need = 0;
+    f3d_attn_bwd_workspace_bytes(n, heads, &need);
+    if (workspace_bytes < need) return F3D_ERR_WORKSPACE_TOO_SMALL;
+    b.f.out = (uint16_t*)const_cast<void*>(out);
+    b.f.lse = const_cast<float*>(lse);
+    b.f.out_perm = grad_perm;
+    b.dout = (const uint16_t*)dout;
+    b.dsum = (float*)workspace;
+    b.dq = (uint16_t*)dq;
+    b.dk = (uint16_t*)dk;
+    b.dv = (uint16_t*)dv;
+    b.scale = scale;
+    b.f.qblocks = (bucket_cap + 127) / 128;
+    b.kblocks = b.f.qblocks;
+    if (slots * heads * b.f.qblocks > 2000000000ll) return F3D_ERR_UNSUPPORTED;
+    b.f.n_slots = (int)slots;
+    (void)hipGetLastError();
+    const hipError_t e = f3d::attn_bwd_launch(b, head_dim, (hipStream_t)stream);
     return e == hipSuccess ? F3D_OK : hip_fail(e);
 }
 

@@ -314,6 +314,86 @@ def test_attention_log_sum_exp_output():
             assert np.abs(lse.cpu().numpy() - want).max() <= 4e-3
 
 
+# ----------------------------------------------------------------------------- attention backward
+
+
+def bwd_case(q, k, v, g, bk, ref_layout, heads, d, mode, use_perm, scope_sel=None, shift=2, stride=2):
+    """Forward (with log-sum-exp) and backward on the GPU against the binary64 gradient of the oracle.
+    Bound: 8e-3 * max(1, max|gradient|) per tensor: the bf16 rounding of the stored gradient is up to 2^-9 relative
+    (4.7e-3 at |g| = 2.4), the bf16 roundings of P and dS and of the forward output inside D add about 1e-3."""
+    n = q.shape[0]
+    tq, tk, tv, tg = (dev(x, torch.bfloat16) for x in (q, k, v, g))
+    lse = torch.empty(n, heads, dtype=torch.float32, device=DEV)
+    out = f3d.bucket_swin_attn(tq, tk, tv, bk, heads, d, mode, shift, stride, use_perm, lse=lse)
+    grads = f3d.bucket_swin_attn_bwd(tq, tk, tv, out, tg, lse, bk, heads, d, mode, shift, stride, use_perm)
+    torch.cuda.synchronize()
+    want = oracle.attn_bwd(q, k, v, g, ref_layout["perm"] if use_perm else None, ref_layout["offsets"],
+                           ref_layout["scan_bucket_start"], bk.scope_buckets, mode, heads, d, shift, stride, scope_sel=scope_sel)
+    rows = want["done"].astype(bool)
+    assert rows.any()
+    for name, got in zip(("dq", "dk", "dv"), grads):
+        gg = got.float().cpu().numpy().astype(np.float64)
+        assert np.isfinite(gg).all()
+        err = np.abs(gg[rows] - want[name][rows])
+        top = max(1.0, float(np.abs(want[name][rows]).max()))
+        assert err.max() <= 8e-3 * top, f"{name}: max-abs {err.max():.4g} > {8e-3 * top:.4g}"
+        assert err.mean() <= 6e-4 * top
+    return grads
+
+
+@pytest.mark.parametrize("d,heads", [(16, 2), (32, 2), (16, 5)])
+def test_attention_backward_ragged_buckets_all_modes(d, heads):
+    sizes = [[64, 64, 37, 64, 1, 64, 64, 64, 50], [17], [64, 64, 64, 64, 64, 3]]
+    bk, ref, n = hand_layout(sizes, 256, 4)
+    rng = np.random.default_rng(60)
+    q, k, v, g = (wl.f32_to_bf16_bits(rng.standard_normal((n, heads * d)).astype(np.float32)) for _ in range(4))
+    for mode, kw in (("plain", {}), ("shift", {"shift": 1}), ("shift", {"shift": 3}), ("stride", {"stride": 2}), ("stride", {"stride": 3})):
+        bwd_case(q, k, v, g, bk, ref, heads, d, mode, True, **kw)
+        bwd_case(q, k, v, g, bk, ref, heads, d, mode, False, **kw)
+
+
+def test_attention_backward_other_scope_shapes():
+    rng = np.random.default_rng(61)
+    for cap, m, sizes in ((32, 2, [[16] * 9 + [5]]), (512, 8, [[64] * 21 + [9]]), (2048, 1, [[2048, 700]]), (1024, 16, [[64] * 40])):
+        bk, ref, n = hand_layout(sizes, cap, m)
+        q, k, v, g = (wl.f32_to_bf16_bits(rng.standard_normal((n, 32)).astype(np.float32)) for _ in range(4))
+        modes = ["plain", "stride"] + (["shift"] if m > 1 else [])
+        for mode in modes:
+            bwd_case(q, k, v, g, bk, ref, 2, 16, mode, True, shift=max(1, m // 2))
+
+
+@pytest.mark.parametrize("name", ["indoor", "lidar8"])
+def test_attention_backward_full_size_sampled_scopes(name):
+    # the launch configuration the benchmark times; the oracle computes the scopes of a few sampled rows in full
+    w = wl.make_workload(name)
+    bk, ref = check_bucketize(w.coords, w.batch_offsets, w.voxel_size, w.bucket_cap)
+    q, k, v = w.qkv()
+    rng = np.random.default_rng(62)
+    g = wl.f32_to_bf16_bits(rng.standard_normal(q.shape).astype(np.float32))
+    bucket_major = name == "lidar8"
+    if bucket_major:
+        q, k, v = q[ref["perm"]], k[ref["perm"]], v[ref["perm"]]
+    for mode in dict.fromkeys(w.modes):
+        sel = np.zeros(w.n, dtype=np.uint8)
+        sel[[0, w.n // 2, w.n - 1]] = 1          # first, middle and last (ragged) scope
+        bwd_case(q, k, v, g, bk, ref, w.heads, w.head_dim, mode, not bucket_major, scope_sel=sel)
+
+
+def test_attention_backward_peaked_softmax_and_input_order():
+    bk, ref, n = hand_layout([[64] * 8], 256, 4)
+    rng = np.random.default_rng(63)
+    q, k, v, g = (wl.f32_to_bf16_bits((rng.standard_normal((n, 32)) * s).astype(np.float32)) for s in (6.0, 6.0, 1.0, 1.0))
+    dq, dk, dv = bwd_case(q, k, v, g, bk, ref, 2, 16, "plain", True)
+    # gradients stored in the input order of the points: the same rows, moved by perm
+    tq, tk, tv, tg = (dev(x, torch.bfloat16) for x in (q, k, v, g))
+    lse = torch.empty(n, 2, dtype=torch.float32, device=DEV)
+    out = f3d.bucket_swin_attn(tq, tk, tv, bk, 2, 16, "plain", lse=lse)
+    eq, ek, ev = f3d.bucket_swin_attn_bwd(tq, tk, tv, out, tg, lse, bk, 2, 16, "plain", original_order=True)
+    torch.cuda.synchronize()
+    for a_, b_ in ((dq, eq), (dk, ek), (dv, ev)):
+        assert torch.equal(f3d.unpermute(a_, bk.perm), b_)
+
+
 # ----------------------------------------------------------------------------- unpermute, end to end
 
 
