@@ -119,6 +119,8 @@ def main() -> int:
                     help="run f3d_unpermute as a kernel of its own instead of folding it into the last pass's store")
     ap.add_argument("--pool", type=int, default=0, metavar="RHO",
                     help="also time f3d_inbucket_pool (mean, tiles of 1024 rows, this reduction factor) on the attention output")
+    ap.add_argument("--backward", action="store_true",
+                    help="also time f3d_bucket_swin_attn_bwd (after a forward that stores the log-sum-exp) for every pass")
     ap.add_argument("--ceilings", action="store_true",
                     help="also run the register-only issue-rate microbenchmark (MFMA only, softmax only, the attention "
                          "tile loop) and add its rates to the JSON line")
@@ -263,6 +265,29 @@ def main() -> int:
         res["pool"] = {"rho": rho, "tile": 1024, "op": "mean", "pooled_rows": n_out, "ms": ms, "points_per_s": n / (ms * 1e-3),
                        "roofline": {"bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                                     "frac": gbps / PEAK_HBM_GBPS, "bytes": nbytes}}
+    if args.backward:   # training: gradient of every pass, outside the headline step
+        lse = torch.empty(n, H, dtype=torch.float32, device=dev)
+        dout = torch.randn(n, C, device=dev, generator=gen, dtype=torch.float32).to(torch.bfloat16)
+        bws = torch.empty(n * H * 4 + 512, dtype=torch.uint8, device=dev)
+        per_mode = {}
+        for mode in dict.fromkeys(w.modes):
+            f3d.bucket_swin_attn(q, k, v, bk, H, d, mode, 2, 2, not bucket_major, 0.0, out, lse=lse)
+            f3d.bucket_swin_attn_bwd(q, k, v, out, dout, lse, bk, H, d, mode, 2, 2, not bucket_major, workspace=bws)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                f3d.bucket_swin_attn_bwd(q, k, v, out, dout, lse, bk, H, d, mode, 2, 2, not bucket_major, workspace=bws)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / args.steps
+            fl = 2.5 * flops[mode]   # five products of 2 n_g^2 d each per head, against the forward's two
+            per_mode[mode] = {"ms": ms, "tflops": fl / (ms * 1e-3) / 1e12, "flop": fl}
+        mean_tf = float(np.mean([x["tflops"] for x in per_mode.values()]))
+        res["backward"] = {"per_mode": per_mode,
+                           "roofline": {"bound": "mfma", "achieved": mean_tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                                        "frac": mean_tf / PEAK_BF16_TFLOPS},
+                           "note": "algorithmic FLOP = 2.5 x forward; the two kernels recompute S and dP, which is not counted"}
     if args.ceilings:
         res["ceilings"] = measured_ceilings(d)
     cpu_rows = args.cpu_rows

@@ -104,21 +104,34 @@ __device__ __forceinline__ void scale_split(const U4& x, float c, U4& hi, U4& lo
     }
 }
 
+// A row's log-sum-exp (in log2 units) and D as bf16 head + remainder pairs: {L_hi, L_lo}, {D_hi, D_lo}. One more MFMA
+// whose other operand holds -1 at the matching two positions subtracts them from a whole score tile (error 2^-17
+// relative), which is cheaper than 16 subtractions per lane and tile on the vector ALU.
+__device__ __forceinline__ uint2 split_pairs(float l2, float dsum)
+{
+    const uint32_t lh = pack_bf16(l2, dsum);   // heads: l2 in the low half, dsum in the high half
+    const float lr = l2 - __uint_as_float(lh << 16), dr = dsum - __uint_as_float(lh & 0xFFFF0000u);
+    const uint32_t lo = pack_bf16(lr, dr);
+    // regroup to {L_hi, L_lo} and {D_hi, D_lo}
+    return make_uint2((lh & 0xFFFFu) | (lo << 16), (lh >> 16) | (lo & 0xFFFF0000u));
+}
+
 // store one 16-byte piece of a row transposed into a [rows of dims][VSTR] array, at the column the MFMA result order
 // wants for row kk of the stage (see the forward kernel's V^T)
+template <int TS>
 __device__ __forceinline__ void store_transposed(uint16_t* base, int c, int kk, uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3)
 {
     const int w16 = kk & 15;
     const int pos = (kk & ~15) + 8 * ((w16 >> 2) & 1) + 4 * (w16 >> 3) + (w16 & 3);
-    uint16_t* col = base + c * 8 * VSTR + pos;
-    col[0 * VSTR] = (uint16_t)(v0 & 0xFFFFu);
-    col[1 * VSTR] = (uint16_t)(v0 >> 16);
-    col[2 * VSTR] = (uint16_t)(v1 & 0xFFFFu);
-    col[3 * VSTR] = (uint16_t)(v1 >> 16);
-    col[4 * VSTR] = (uint16_t)(v2 & 0xFFFFu);
-    col[5 * VSTR] = (uint16_t)(v2 >> 16);
-    col[6 * VSTR] = (uint16_t)(v3 & 0xFFFFu);
-    col[7 * VSTR] = (uint16_t)(v3 >> 16);
+    uint16_t* col = base + c * 8 * TS + pos;
+    col[0 * TS] = (uint16_t)(v0 & 0xFFFFu);
+    col[1 * TS] = (uint16_t)(v0 >> 16);
+    col[2 * TS] = (uint16_t)(v1 & 0xFFFFu);
+    col[3 * TS] = (uint16_t)(v1 >> 16);
+    col[4 * TS] = (uint16_t)(v2 & 0xFFFFu);
+    col[5 * TS] = (uint16_t)(v2 >> 16);
+    col[6 * TS] = (uint16_t)(v3 & 0xFFFFu);
+    col[7 * TS] = (uint16_t)(v3 >> 16);
 }
 
 template <int D>
@@ -141,6 +154,9 @@ constexpr int TROWS16 = 17;   // head_dim 16: 16 rows of a transposed operand pl
 
 template <int D>
 constexpr int trows() { return D == 16 ? TROWS16 : D; }
+
+template <int D>
+constexpr int dkdv_stage_rows() { return D == 32 ? 64 : 128; }
 
 // ------------------------------------------------------------------------------------------------
 // dQ. dynamic LDS per buffer: K rows [KT*D] | V rows [KT*D] | K^T [trows][VSTR]   (bf16), two buffers
@@ -169,7 +185,11 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dq(AttnBwdArgs b)
     const bool qok = xq < ng;
     const int orow = qok ? seg_row_of(sm, seg_pre, seg_row0, xq) : -1;
     U4 qhi[KS], qlo[KS], dof[KS];
-    float L2 = 0.f, Dq = 0.f;
+    U4 ext;         // B operand that carries this query's log-sum-exp and D (lower half-wave: k positions 0..3)
+    U4 negS, negD;  // A operands with -1 at the positions of the log-sum-exp pair / the D pair
+    ext.u = make_uint4(0, 0, 0, 0);
+    negS.u = make_uint4(hf == 0 ? 0xBF80BF80u : 0u, 0, 0, 0);
+    negD.u = make_uint4(0, hf == 0 ? 0xBF80BF80u : 0u, 0, 0);
     {
         const size_t gr = qok ? (size_t)(a.perm ? a.perm[orow] : orow) : 0;
 #pragma unroll
@@ -183,9 +203,10 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dq(AttnBwdArgs b)
             }
             scale_split(qf, a.c_log2, qhi[ks], qlo[ks]);
         }
-        if (qok) {
-            L2 = a.lse[(size_t)orow * a.H + head] * LOG2E;
-            Dq = b.dsum[(size_t)orow * a.H + head];
+        if (qok && hf == 0) {
+            const uint2 pr = split_pairs(a.lse[(size_t)orow * a.H + head] * LOG2E, b.dsum[(size_t)orow * a.H + head]);
+            ext.u.x = pr.x;
+            ext.u.y = pr.y;
         }
     }
 
@@ -230,7 +251,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dq(AttnBwdArgs b)
             u32x4 kw = {k0, k1, k2, k3};
             *reinterpret_cast<u32x4*>(&sK[kk * D + cs * 8]) = kw;
             *reinterpret_cast<u32x4*>(&sVr[kk * D + cs * 8]) = vreg[i];
-            store_transposed(sKT, c, kk, k0, k1, k2, k3);
+            store_transposed<VSTR>(sKT, c, kk, k0, k1, k2, k3);
         }
     };
     if (D == 16)   // the zeros row of K^T
@@ -275,6 +296,8 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dq(AttnBwdArgs b)
                 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.b, qlo[ks].b, s, 0, 0, 0);
                 dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.b, dof[ks].b, dp, 0, 0, 0);
             }
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(negS.b, ext.b, s, 0, 0, 0);     // score - lse
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(negD.b, ext.b, dp, 0, 0, 0);   // dP - D
             U4 kt0, kt1;
             kt0.u = *reinterpret_cast<const uint4*>(&sKT[t4 * 32]);
             kt1.u = *reinterpret_cast<const uint4*>(&sKT[t4 * 32 + 16]);
@@ -285,9 +308,9 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dq(AttnBwdArgs b)
                     if (key >= ng) s[r] = -INFINITY;
                 }
             }
-            // dS^T = P o (dP^T - D), P = 2^(score - lse): all per-lane scalars in this orientation
+            // dS^T = P o (dP^T - D), P = 2^(score - lse)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(s[r] - L2) * (dp[r] - Dq);
+            for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(s[r]) * dp[r];
             union { uint32_t u[4]; bf16x8 b; } pb0, pb1;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -305,13 +328,15 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dq(AttnBwdArgs b)
 
 // ------------------------------------------------------------------------------------------------
 // dK and dV. dynamic LDS per buffer: Q rows [KT*D] | dO rows [KT*D] | Q^T [trows][VSTR] | dO^T [trows][VSTR] (bf16) |
-// lse*log2e [KT] | D [KT] (binary32), two buffers
+// per row 16 bytes {lse*log2e hi, lo, D hi, lo, 0 x 4} [KT], two buffers
 template <int D>
 __global__ __launch_bounds__(256) void k_attn_bwd_dkdv(AttnBwdArgs b)
 {
+    constexpr int KT = dkdv_stage_rows<D>();   // query rows per stage: 64 at head_dim 32 keeps three workgroups per CU
+    constexpr int VSTR = KT + 8;
     constexpr int NC = D / 8, KS = D / 16, LPT = KT * NC / 256;
     constexpr int SWZ_SHIFT = (NC == 2) ? 3 : 2;
-    constexpr int BUF = 2 * KT * D + 2 * trows<D>() * VSTR + 4 * KT;   // 16-bit elements per buffer (the floats take 2 each)
+    constexpr int BUF = 2 * KT * D + 2 * trows<D>() * VSTR + 8 * KT;   // 16-bit elements per buffer
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     __shared__ int seg_row0[MAXSEG];
     __shared__ int seg_pre[MAXSEG + 1];
@@ -331,6 +356,9 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkdv(AttnBwdArgs b)
     const bool kok = xk < ng;
     const int krow = kok ? seg_row_of(sm, seg_pre, seg_row0, xk) : -1;
     U4 khi[KS], klo[KS], vfr[KS];
+    U4 negS, negD;   // B operands with -1 at the positions of a staged row's log-sum-exp pair / D pair
+    negS.u = make_uint4(hf == 0 ? 0xBF80BF80u : 0u, 0, 0, 0);
+    negD.u = make_uint4(0, hf == 0 ? 0xBF80BF80u : 0u, 0, 0);
     {
         const size_t gr = kok ? (size_t)(a.perm ? a.perm[krow] : krow) : 0;
 #pragma unroll
@@ -379,8 +407,8 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkdv(AttnBwdArgs b)
             greg[i] = *reinterpret_cast<const u32x4*>(gthr[i] + (uint64_t)brow_next[i] * row_bytes);
         }
         if (tid < KT) {
-            // a position past the end of the scope gets lse = +inf: its probabilities are exactly zero
-            lreg = lrow_next >= 0 ? a.lse[(size_t)lrow_next * a.H + head] * LOG2E : INFINITY;
+            // a position past the end of the scope gets a huge lse: its probabilities are exactly zero
+            lreg = lrow_next >= 0 ? a.lse[(size_t)lrow_next * a.H + head] * LOG2E : 1e30f;
             dreg = lrow_next >= 0 ? b.dsum[(size_t)lrow_next * a.H + head] : 0.f;
         }
     };
@@ -389,8 +417,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkdv(AttnBwdArgs b)
         uint16_t* sG = sQ + KT * D;
         uint16_t* sQT = sG + KT * D;
         uint16_t* sGT = sQT + trows<D>() * VSTR;
-        float* sL = reinterpret_cast<float*>(sGT + trows<D>() * VSTR);
-        float* sD = sL + KT;
+        uint4* sX = reinterpret_cast<uint4*>(sGT + trows<D>() * VSTR);
 #pragma unroll
         for (int i = 0; i < LPT; ++i) {
             uint32_t q0 = qreg[i].x, q1 = qreg[i].y, q2 = qreg[i].z, q3 = qreg[i].w;
@@ -402,12 +429,12 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkdv(AttnBwdArgs b)
             u32x4 qw = {q0, q1, q2, q3}, gw = {g0, g1, g2, g3};
             *reinterpret_cast<u32x4*>(&sQ[kk * D + cs * 8]) = qw;
             *reinterpret_cast<u32x4*>(&sG[kk * D + cs * 8]) = gw;
-            store_transposed(sQT, c, kk, q0, q1, q2, q3);
-            store_transposed(sGT, c, kk, g0, g1, g2, g3);
+            store_transposed<VSTR>(sQT, c, kk, q0, q1, q2, q3);
+            store_transposed<VSTR>(sGT, c, kk, g0, g1, g2, g3);
         }
         if (tid < KT) {
-            sL[tid] = lreg;
-            sD[tid] = dreg;
+            const uint2 pr = split_pairs(lreg, dreg);
+            sX[tid] = make_uint4(pr.x, pr.y, 0, 0);
         }
     };
     if (D == 16)   // the zeros rows of Q^T and dO^T
@@ -437,8 +464,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkdv(AttnBwdArgs b)
         const uint16_t* sG = sQ + KT * D;
         const uint16_t* sQT = sG + KT * D + toff;
         const uint16_t* sGT = sQT + trows<D>() * VSTR;
-        const float* sL = reinterpret_cast<const float*>(smem + buf * BUF + 2 * KT * D + 2 * trows<D>() * VSTR);
-        const float* sD = sL + KT;
+        const uint4* sX = reinterpret_cast<const uint4*>(smem + buf * BUF + 2 * KT * D + 2 * trows<D>() * VSTR);
 #pragma unroll 2
         for (int t4 = 0; t4 < KT / 32; ++t4) {
             const int qbase = st * KT + t4 * 32;
@@ -456,24 +482,23 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkdv(AttnBwdArgs b)
                 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf.b, klo[ks].b, s, 0, 0, 0);
                 dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf.b, vfr[ks].b, dp, 0, 0, 0);
             }
+            {   // subtract every query's log-sum-exp from its score row and its D from its dP row on the matrix core
+                U4 xf;
+                xf.u = sX[qq];
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf.b, negS.b, s, 0, 0, 0);
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf.b, negD.b, dp, 0, 0, 0);
+            }
             U4 qt0, qt1, gt0, gt1;
             qt0.u = *reinterpret_cast<const uint4*>(&sQT[t4 * 32]);
             qt1.u = *reinterpret_cast<const uint4*>(&sQT[t4 * 32 + 16]);
             gt0.u = *reinterpret_cast<const uint4*>(&sGT[t4 * 32]);
             gt1.u = *reinterpret_cast<const uint4*>(&sGT[t4 * 32 + 16]);
-            // a lane holds one key (column) and the 16 queries 8j + 4 hf + r of the tile: their lse and D come from LDS
+            // P = 2^(score - lse), dS = P o (dP - D)
             f32x16 p;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float4 l4 = *reinterpret_cast<const float4*>(&sL[t4 * 32 + 8 * j + 4 * hf]);
-                const float4 d4 = *reinterpret_cast<const float4*>(&sD[t4 * 32 + 8 * j + 4 * hf]);
-                const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dvv[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float pr = __builtin_amdgcn_exp2f(s[4 * j + r] - lv[r]);
-                    p[4 * j + r] = pr;
-                    s[4 * j + r] = pr * (dp[4 * j + r] - dvv[r]);
-                }
+            for (int r = 0; r < 16; ++r) {
+                p[r] = __builtin_amdgcn_exp2f(s[r]);
+                s[r] = p[r] * dp[r];
             }
             union { uint32_t u[4]; bf16x8 b; } pb0, pb1, sb0, sb1;
 #pragma unroll
@@ -502,7 +527,8 @@ hipError_t launch_d(const AttnBwdArgs& b, hipStream_t stream)
     const long long rows = (long long)a.n * a.H;
     if (rows > 0) k_attn_bwd_pre<<<(unsigned)((rows + 255) / 256), 256, 0, stream>>>(b, D);
     const size_t lds_dq = (size_t)2 * (2 * KT * D + trows<D>() * VSTR) * 2;
-    const size_t lds_kv = (size_t)2 * (2 * KT * D + 2 * trows<D>() * VSTR + 4 * KT) * 2;
+    constexpr int KB = dkdv_stage_rows<D>();
+    const size_t lds_kv = (size_t)2 * (2 * KB * D + 2 * trows<D>() * (KB + 8) + 8 * KB) * 2;
     hipError_t e = hipFuncSetAttribute((const void*)k_attn_bwd_dq<D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_dq);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute((const void*)k_attn_bwd_dkdv<D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_kv);
