@@ -202,5 +202,39 @@ def pool_reduce(feat_bm: np.ndarray, sub_of: np.ndarray, n_out: int, op: str = "
     return res
 
 
+def _bf16_bits_to_f64(a: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(a, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def ln_linear(x: np.ndarray, w: np.ndarray, bias: Optional[np.ndarray] = None, gamma: Optional[np.ndarray] = None,
+              beta: Optional[np.ndarray] = None, eps: float = 1e-5, row_in: Optional[np.ndarray] = None,
+              residual: Optional[np.ndarray] = None, row_out: Optional[np.ndarray] = None) -> np.ndarray:
+    """The point-wise part of a transformer block around the attention (Section 4.2, block equations: LayerNorm and
+    the linear maps of MHSA / MLP applied to every point), in binary64:
+        y[p] = LN(x[row_in[p]]) @ w.T + bias,   LN(v) = (v - mean(v)) / sqrt(var(v) + eps) * gamma + beta  (biased variance)
+        out[row_out[p]] = y[p] + residual[row_out[p]]
+    x: uint16 bf16 bits [n, c_in]; w: uint16 bf16 bits [c_out, c_in]; gamma/beta/bias: float arrays; gamma=None skips
+    the LayerNorm; residual: uint16 bf16 bits [n, c_out] or None. Returns float64 [n, c_out]."""
+    xf = _bf16_bits_to_f64(x)
+    if row_in is not None:
+        xf = xf[np.asarray(row_in, dtype=np.int64)]
+    if gamma is not None:
+        mu = xf.mean(axis=1, keepdims=True)
+        var = ((xf - mu) ** 2).mean(axis=1, keepdims=True)
+        xf = (xf - mu) / np.sqrt(var + eps) * np.asarray(gamma, dtype=np.float64)
+        if beta is not None:
+            xf = xf + np.asarray(beta, dtype=np.float64)
+    y = xf @ _bf16_bits_to_f64(w).T
+    if bias is not None:
+        y = y + np.asarray(bias, dtype=np.float64)
+    out = y
+    if row_out is not None:
+        out = np.empty_like(y)
+        out[np.asarray(row_out, dtype=np.int64)] = y
+    if residual is not None:
+        out = out + _bf16_bits_to_f64(residual)
+    return out
+
+
 def max_threads() -> int:
     return int(lib().orc_max_threads())
