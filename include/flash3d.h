@@ -184,6 +184,28 @@ int f3d_bucket_swin_attn_bwd(const void *q, const void *k, const void *v, const 
                              const int32_t *grad_perm, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The point-wise glue of a transformer block (Section 4.2, block equations F' = MHSA(LN(F)) + F, F~ = MLP(LN(F')) + F';
+ * Section 4.1 "Stage Orchestration"): LayerNorm and a linear map over every row in one pass, with the row gather that
+ * writes q, k, v in bucket-major order and the row scatter + residual that brings a block's output back.
+ *     y[p] = LN(x[row_in[p]]) W^T + bias,   LN(v) = (v - mean v) / sqrt(var v + eps) * gamma + beta  (biased variance)
+ *     out[row_out[p]] = y[p] + residual[row_out[p]]
+ *   x         bf16 [n, c_in], 16-byte aligned;  c_in is 64, 128 or 256
+ *   row_in    NULL (row p reads x[p]) or [n] int32, e.g. perm: the outputs come out bucket-major
+ *   gamma, beta  binary32 [c_in], 16-byte aligned; gamma NULL skips the LayerNorm (then beta must be NULL); beta may be NULL
+ *   w         bf16 [c_out, c_in] (one row per output column), 16-byte aligned;  bias  binary32 [c_out] or NULL
+ *   residual  NULL or bf16 [n, c_out], indexed by the DESTINATION row
+ *   c_out     multiple of 64, at most 4096
+ *   outs      HOST array of n_outs (1..4) DEVICE pointers: the c_out columns are split evenly over bf16 [n, c_out/n_outs]
+ *             tensors (three for q, k, v); c_out / n_outs must be a multiple of 8
+ *   row_out   NULL or [n] int32, a permutation: output row p is stored at row row_out[p]
+ * Arithmetic: LayerNorm in fp32 on the bf16 input, rounded to bf16; bf16 MFMA with fp32 accumulation; bias and
+ * residual added in fp32; one rounding to bf16.
+ */
+int f3d_ln_linear(const void *x, const int32_t *row_in, const float *gamma, const float *beta, float eps, const void *w,
+                  const float *bias, const void *residual, int64_t n, int32_t c_in, int32_t c_out, void *const *outs,
+                  int32_t n_outs, const int32_t *row_out, void *stream);
+
+/*
  * In-bucket pooling (Section 4.2 "In-bucket Pooling"; Appendix "In-bucket Pooling"): the bucket-major array is
  * cut into tiles of `tile` consecutive rows (tiles start at a scan's first row and never span scans); inside a
  * tile of n rows, M = ceil(n / rho) sub-buckets of capacity rho are built in the Appendix's three steps (initial

@@ -21,7 +21,7 @@ MODES = {"plain": 0, "shift": 1, "stride": 2}
 SCHEDULES = {"auto": 0, "general": 1, "steps": 2}
 
 EXPORTS = ("f3d_params_default", "f3d_max_buckets", "f3d_workspace_bytes", "f3d_psh_bucketize",
-           "f3d_bucket_swin_attn", "f3d_attn_bwd_workspace_bytes", "f3d_bucket_swin_attn_bwd", "f3d_pool_max_rows", "f3d_pool_workspace_bytes", "f3d_inbucket_pool",
+           "f3d_bucket_swin_attn", "f3d_attn_bwd_workspace_bytes", "f3d_bucket_swin_attn_bwd", "f3d_ln_linear", "f3d_pool_max_rows", "f3d_pool_workspace_bytes", "f3d_inbucket_pool",
            "f3d_unpermute", "f3d_error_string", "f3d_last_hip_error", "f3d_version")
 POOL_OPS = {"sum": 0, "mean": 1, "min": 2, "max": 3}
 
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.f3d_bucket_swin_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, i32, i32, i32, i32, i32, i32, f32,
                                                vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.f3d_bucket_swin_attn_bwd.restype = ctypes.c_int
+        L.f3d_ln_linear.argtypes = [vp, vp, vp, vp, f32, vp, vp, vp, i64, i32, i32, ctypes.POINTER(vp), i32, vp, vp]
+        L.f3d_ln_linear.restype = ctypes.c_int
         L.f3d_pool_max_rows.argtypes = [i64, i32, i32, i32]
         L.f3d_pool_max_rows.restype = i64
         L.f3d_pool_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(ctypes.c_size_t)]
@@ -222,6 +224,24 @@ def bucket_swin_attn_bwd(q, k, v, out, dout, lse, buckets: Buckets, heads: int, 
     if rc != F3D_OK:
         raise Flash3DError(rc, "f3d_bucket_swin_attn_bwd")
     return dq, dk, dv
+
+
+def ln_linear(x, w, bias=None, gamma=None, beta=None, eps: float = 1e-5, row_in=None, residual=None, row_out=None,
+              n_outs: int = 1):
+    """f3d_ln_linear on torch CUDA tensors. x bfloat16 [n, c_in]; w bfloat16 [c_out, c_in]; gamma/beta/bias float32.
+    Returns a tuple of n_outs bfloat16 tensors [n, c_out / n_outs]."""
+    import torch
+    n, c_in = int(x.shape[0]), int(x.shape[1])
+    c_out = int(w.shape[0])
+    assert x.is_cuda and x.dtype == torch.bfloat16 and x.is_contiguous()
+    assert w.dtype == torch.bfloat16 and w.is_contiguous() and w.shape[1] == c_in
+    outs = tuple(torch.empty(n, c_out // n_outs, dtype=torch.bfloat16, device=x.device) for _ in range(n_outs))
+    arr = (ctypes.c_void_p * n_outs)(*[t.data_ptr() for t in outs])
+    rc = lib().f3d_ln_linear(_ptr(x), _ptr(row_in), _ptr(gamma), _ptr(beta), eps, _ptr(w), _ptr(bias), _ptr(residual), n, c_in,
+                             c_out, arr, n_outs, _ptr(row_out), _stream())
+    if rc != F3D_OK:
+        raise Flash3DError(rc, "f3d_ln_linear")
+    return outs
 
 
 @dataclass

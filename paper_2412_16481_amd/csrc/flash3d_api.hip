@@ -7,6 +7,7 @@
 
 #include "attn.h"
 #include "flash3d.h"
+#include "linear.h"
 #include "pool.h"
 #include "psh.h"
 
@@ -318,6 +319,46 @@ int f3d_bucket_swin_attn_bwd(const void* q, const void* k, const void* v, const 
     b.f.n_slots = (int)slots;
     (void)hipGetLastError();
     const hipError_t e = f3d::attn_bwd_launch(b, head_dim, (hipStream_t)stream);
+    return e == hipSuccess ? F3D_OK : hip_fail(e);
+}
+
+int f3d_ln_linear(const void* x, const int32_t* row_in, const float* gamma, const float* beta, float eps, const void* w,
+                  const float* bias, const void* residual, int64_t n, int32_t c_in, int32_t c_out, void* const* outs,
+                  int32_t n_outs, const int32_t* row_out, void* stream)
+{
+    if (n < 0 || c_in < 1 || c_out < 1 || n_outs < 1 || !outs) return F3D_ERR_INVALID_ARG;
+    if (n_outs > f3d::LIN_MAX_OUTS || (c_in != 64 && c_in != 128 && c_in != 256)) return F3D_ERR_UNSUPPORTED;
+    if (c_out % 64 != 0 || c_out % n_outs != 0 || (c_out / n_outs) % 8 != 0 || c_out > 4096) return F3D_ERR_UNSUPPORTED;
+    if (n >= (int64_t)2147483647 - (1 << 20)) return F3D_ERR_UNSUPPORTED;
+    if (gamma && !(eps >= 0.0f && isfinite(eps))) return F3D_ERR_INVALID_ARG;
+    if (!gamma && beta) return F3D_ERR_INVALID_ARG;
+    if (n == 0) return F3D_OK;
+    if (!x || !w) return F3D_ERR_INVALID_ARG;
+    if (((uintptr_t)x | (uintptr_t)w | (uintptr_t)residual | (uintptr_t)gamma | (uintptr_t)beta | (uintptr_t)bias) & 15)
+        return F3D_ERR_BAD_ALIGNMENT;
+    if (((uintptr_t)row_in | (uintptr_t)row_out) & 3) return F3D_ERR_BAD_ALIGNMENT;
+    f3d::LinearArgs a;
+    memset(&a, 0, sizeof(a));
+    for (int t = 0; t < n_outs; ++t) {
+        if (!outs[t]) return F3D_ERR_INVALID_ARG;
+        if ((uintptr_t)outs[t] & 15) return F3D_ERR_BAD_ALIGNMENT;
+        a.outs[t] = (uint16_t*)outs[t];
+    }
+    a.x = (const uint16_t*)x;
+    a.row_in = row_in;
+    a.gamma = gamma;
+    a.beta = beta;
+    a.eps = eps;
+    a.w = (const uint16_t*)w;
+    a.bias = bias;
+    a.residual = (const uint16_t*)residual;
+    a.n = (int)n;
+    a.c_in = c_in;
+    a.c_out = c_out;
+    a.n_outs = n_outs;
+    a.row_out = row_out;
+    (void)hipGetLastError();
+    const hipError_t e = f3d::linear_launch(a, (hipStream_t)stream);
     return e == hipSuccess ? F3D_OK : hip_fail(e);
 }
 

@@ -537,3 +537,61 @@ def test_pool_after_attention_end_to_end():
     torch.cuda.synchronize()
     feat_bits = out.view(torch.int16).cpu().numpy().view(np.uint16)
     check_pool(w.coords, ref["perm"], feat_bits, w.batch_offsets, 128, 2, 0.1, "zorder_div", "mean")
+
+
+# ----------------------------------------------------------------------------- LayerNorm + linear (block glue)
+
+
+def check_ln_linear(n, c_in, c_out, n_outs, rng, ln=True, with_bias=True, with_res=False, gather=False, scatter=False):
+    """GPU against the binary64 oracle. Bound per element: 2^-8 |y| for the final bf16 rounding, plus 0.012 for the bf16
+    rounding of the normalised row inside the dot product: c_in terms of size |ln_c w_c| with independent relative errors
+    of 2^-9 give a standard deviation of 2^-9 |ln| |w| / sqrt(c_in) ~ 2.5e-3 for rows of norm sqrt(c_in) and weight rows
+    of norm 1 as generated here; 0.012 is five of those."""
+    x = wl.f32_to_bf16_bits((rng.standard_normal((n, c_in)) * 2 + 0.5).astype(np.float32))
+    w = wl.f32_to_bf16_bits((rng.standard_normal((c_out, c_in)) / np.sqrt(c_in)).astype(np.float32))
+    gamma = (1 + 0.2 * rng.standard_normal(c_in)).astype(np.float32) if ln else None
+    beta = (0.1 * rng.standard_normal(c_in)).astype(np.float32) if ln else None
+    bias = rng.standard_normal(c_out).astype(np.float32) if with_bias else None
+    res = wl.f32_to_bf16_bits(rng.standard_normal((n, c_out)).astype(np.float32)) if with_res else None
+    row_in = rng.permutation(n).astype(np.int32) if gather else None
+    row_out = rng.permutation(n).astype(np.int32) if scatter else None
+    want = oracle.ln_linear(x, w, bias, gamma, beta, 1e-5, row_in, res, row_out)
+    t = lambda a, dt=None: None if a is None else dev(a, dt)
+    outs = f3d.ln_linear(t(x, torch.bfloat16), t(w, torch.bfloat16), t(bias), t(gamma), t(beta), 1e-5, t(row_in),
+                         t(res, torch.bfloat16), t(row_out), n_outs)
+    torch.cuda.synchronize()
+    got = np.concatenate([o.float().cpu().numpy() for o in outs], axis=1).astype(np.float64)
+    assert np.isfinite(got).all()
+    bound = 2.0 ** -8 * np.abs(want) + 0.012 * (1.0 if ln else 2.5)   # without LayerNorm the rows here have norm 2 sqrt(c_in)
+    assert (np.abs(got - want) <= bound).all(), f"max excess {(np.abs(got - want) - bound).max():.4g}"
+    assert np.abs(got - want).mean() <= 4e-3
+
+
+@pytest.mark.parametrize("c_in,c_out,n_outs", [(64, 192, 3), (128, 384, 3), (256, 768, 3), (64, 64, 1), (256, 256, 1), (128, 512, 1)])
+def test_ln_linear_matches_oracle(c_in, c_out, n_outs):
+    rng = np.random.default_rng(80 + c_in)
+    check_ln_linear(1000, c_in, c_out, n_outs, rng, ln=True, gather=True)                                  # q, k, v in bucket-major order
+    check_ln_linear(777, c_in, c_out, n_outs, rng, ln=False, with_res=True, scatter=True)                   # output projection + residual, back in input order
+    check_ln_linear(129, c_in, c_out, n_outs, rng, ln=True, with_bias=False, with_res=True, gather=True, scatter=True)
+
+
+def test_ln_linear_edge_sizes_and_block_composition():
+    rng = np.random.default_rng(81)
+    for n in (1, 127, 128, 129, 4096):
+        check_ln_linear(n, 64, 192, 3, rng, gather=True)
+    # empty input
+    outs = f3d.ln_linear(torch.empty(0, 64, dtype=torch.bfloat16, device=DEV), dev(np.zeros((64, 64), np.uint16), torch.bfloat16))
+    assert outs[0].shape == (0, 64)
+    # the first half of a block on the tiny workload: q, k, v written bucket-major feed the attention without a gather
+    w_ = wl.make_workload("tiny")
+    bk, ref = check_bucketize(w_.coords, w_.batch_offsets, w_.voxel_size, w_.bucket_cap)
+    C = w_.channels
+    feat = wl.f32_to_bf16_bits(rng.standard_normal((w_.n, C)).astype(np.float32))
+    wq = wl.f32_to_bf16_bits((rng.standard_normal((3 * C, C)) / np.sqrt(C)).astype(np.float32))
+    gamma, beta = np.ones(C, np.float32), np.zeros(C, np.float32)
+    q, k, v = f3d.ln_linear(dev(feat, torch.bfloat16), dev(wq, torch.bfloat16), None, dev(gamma), dev(beta), 1e-5, bk.perm, n_outs=3)
+    out = f3d.bucket_swin_attn(q, k, v, bk, w_.heads, w_.head_dim, "shift", use_perm=False)
+    torch.cuda.synchronize()
+    bits = lambda t_: t_.view(torch.int16).cpu().numpy().view(np.uint16)
+    want = oracle.attn(bits(q), bits(k), bits(v), None, ref["offsets"], ref["scan_bucket_start"], 4, "shift", w_.heads, w_.head_dim)
+    assert np.abs(out.float().cpu().numpy() - want).max() <= ATOL
