@@ -121,6 +121,9 @@ def main() -> int:
                     help="also time f3d_inbucket_pool (mean, tiles of 1024 rows, this reduction factor) on the attention output")
     ap.add_argument("--backward", action="store_true",
                     help="also time f3d_bucket_swin_attn_bwd (after a forward that stores the log-sum-exp) for every pass")
+    ap.add_argument("--glue", action="store_true",
+                    help="also time f3d_ln_linear as the block's QKV projection (LayerNorm, rows gathered into bucket-major "
+                         "order) and as its output projection (residual, rows scattered back)")
     ap.add_argument("--ceilings", action="store_true",
                     help="also run the register-only issue-rate microbenchmark (MFMA only, softmax only, the attention "
                          "tile loop) and add its rates to the JSON line")
@@ -288,6 +291,35 @@ def main() -> int:
                            "roofline": {"bound": "mfma", "achieved": mean_tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                                         "frac": mean_tf / PEAK_BF16_TFLOPS},
                            "note": "algorithmic FLOP = 2.5 x forward; the two kernels recompute S and dP, which is not counted"}
+    if args.glue:
+        feat = torch.randn(n, C, device=dev, generator=gen, dtype=torch.float32).to(torch.bfloat16)
+        wqkv = (torch.randn(3 * C, C, device=dev, generator=gen, dtype=torch.float32) / C ** 0.5).to(torch.bfloat16)
+        wo = (torch.randn(C, C, device=dev, generator=gen, dtype=torch.float32) / C ** 0.5).to(torch.bfloat16)
+        gamma, beta = torch.ones(C, device=dev), torch.zeros(C, device=dev)
+        bqkv, bo_ = torch.zeros(3 * C, device=dev), torch.zeros(C, device=dev)
+
+        def timed(fn):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / args.steps
+
+        ms_qkv = timed(lambda: f3d.ln_linear(feat, wqkv, bqkv, gamma, beta, 1e-5, bk.perm, n_outs=3))
+        ms_out = timed(lambda: f3d.ln_linear(out, wo, bo_, None, None, 0.0, None, feat, bk.perm))
+        by_qkv = n * (2 * C + 4 + 3 * 2 * C)            # features and perm read, q, k, v written
+        by_out = n * (2 * C + 4 + 2 * C + 2 * C)        # attention output and perm read, residual read, result written
+        res["glue"] = {
+            "qkv": {"ms": ms_qkv, "tflops": 2.0 * n * C * 3 * C / (ms_qkv * 1e-3) / 1e12,
+                    "roofline": {"bound": "hbm", "achieved": by_qkv / (ms_qkv * 1e-3) / 1e9, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                 "frac": by_qkv / (ms_qkv * 1e-3) / 1e9 / PEAK_HBM_GBPS, "bytes": by_qkv}},
+            "out_proj": {"ms": ms_out, "tflops": 2.0 * n * C * C / (ms_out * 1e-3) / 1e12,
+                         "roofline": {"bound": "hbm", "achieved": by_out / (ms_out * 1e-3) / 1e9, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                      "frac": by_out / (ms_out * 1e-3) / 1e9 / PEAK_HBM_GBPS, "bytes": by_out}}}
     if args.ceilings:
         res["ceilings"] = measured_ceilings(d)
     cpu_rows = args.cpu_rows

@@ -5,9 +5,9 @@
 //
 //   y[p] = LN(x[row_in[p]]) W^T + bias;   out[row_out[p]] = y[p] + residual[row_out[p]]
 //
-// One workgroup = 128 rows. The rows are normalised in registers (two threads per row), rounded to bf16 and kept in
-// LDS for the whole workgroup; the weight matrix (at most 768 x 256 bf16, resident in L2) is read straight from
-// memory as the A operand of v_mfma_f32_32x32x16_bf16 computing the TRANSPOSED product Y^T = W X^T, so that a lane
+// One workgroup = 128 rows. The rows are normalised in place in LDS (two threads per row), rounded to bf16 and kept in
+// LDS for the whole workgroup; the weight matrix (resident in L2) is read straight from memory, once per workgroup,
+// as the A operand of v_mfma_f32_32x32x16_bf16 computing the TRANSPOSED product Y^T = W X^T, so that a lane
 // owns one row of Y and four consecutive columns per register group: 8-byte stores, no shuffles.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -104,47 +104,55 @@ __global__ __launch_bounds__(256) void k_ln_linear(LinearArgs a)
     }
     __syncthreads();
 
-    // ---- Y^T tile by tile: wave w owns rows 32w .. 32w+31 of the workgroup and walks over all output columns,
-    //      two 32-column blocks at a time (the X fragment of a k-step is read from LDS once for both)
-    const long long p = row0 + wave * 32 + l32;          // this lane's row of Y
-    const bool ok = p < a.n;
-    const size_t drow = ok ? (size_t)(a.row_out ? a.row_out[p] : p) : 0;
+    // ---- Y^T block by block: a wave takes every fourth 32-column block of the output and computes it for ALL 128 rows
+    //      of the workgroup, so the workgroup reads every row of W exactly once (from L2) while the normalised rows
+    //      are re-read from LDS.
+    size_t drow[4];
+    bool ok[4];
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) {
+        const long long p = row0 + rb * 32 + l32;          // this lane's row of Y in row block rb
+        ok[rb] = p < a.n;
+        drow[rb] = ok[rb] ? (size_t)(a.row_out ? a.row_out[p] : p) : 0;
+    }
     const int per_out = a.c_out / a.n_outs;
-    const uint16_t* xrow = &sx[(wave * 32 + l32) * PITCH + 8 * hf];
-    for (int col0 = 0; col0 < a.c_out; col0 += 64) {
-        f32x16 acc0 = {0}, acc1 = {0};
-        const uint16_t* w0 = a.w + (size_t)(col0 + l32) * CI + 8 * hf;   // rows of W = output columns
-        const uint16_t* w1 = w0 + (size_t)32 * CI;
+    const uint16_t* xrow = &sx[l32 * PITCH + 8 * hf];
+    for (int col0 = 32 * wave; col0 < a.c_out; col0 += 128) {
+        f32x16 acc[4];
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) acc[rb] = f32x16{0};
+        const uint16_t* wr = a.w + (size_t)(col0 + l32) * CI + 8 * hf;   // rows of W = output columns
 #pragma unroll 2
         for (int ks = 0; ks < KS; ++ks) {
-            F8 xf, wa, wb;
-            xf.u = *reinterpret_cast<const uint4*>(xrow + 16 * ks);
-            wa.u = *reinterpret_cast<const uint4*>(w0 + 16 * ks);
-            wb.u = *reinterpret_cast<const uint4*>(w1 + 16 * ks);
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa.b, xf.b, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb.b, xf.b, acc1, 0, 0, 0);
-        }
-        if (!ok) continue;
+            F8 wa;
+            wa.u = *reinterpret_cast<const uint4*>(wr + 16 * ks);
 #pragma unroll
-        for (int blk = 0; blk < 2; ++blk) {
-            const f32x16& acc = blk ? acc1 : acc0;
+            for (int rb = 0; rb < 4; ++rb) {
+                F8 xf;
+                xf.u = *reinterpret_cast<const uint4*>(xrow + rb * 32 * PITCH + 16 * ks);
+                acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa.b, xf.b, acc[rb], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+            if (!ok[rb]) continue;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int col = col0 + 32 * blk + 8 * j + 4 * hf;        // four consecutive columns of this lane's row
-                float y[4] = {acc[4 * j], acc[4 * j + 1], acc[4 * j + 2], acc[4 * j + 3]};
+                const int col = col0 + 8 * j + 4 * hf;        // four consecutive columns of this lane's row
+                float y[4] = {acc[rb][4 * j], acc[rb][4 * j + 1], acc[rb][4 * j + 2], acc[rb][4 * j + 3]};
                 if (a.bias) {
                     const float4 bv = *reinterpret_cast<const float4*>(a.bias + col);
                     y[0] += bv.x; y[1] += bv.y; y[2] += bv.z; y[3] += bv.w;
                 }
                 if (a.residual) {
-                    const uint2 rv = *reinterpret_cast<const uint2*>(a.residual + drow * a.c_out + col);
+                    const uint2 rv = *reinterpret_cast<const uint2*>(a.residual + drow[rb] * a.c_out + col);
                     y[0] += lo16(rv.x); y[1] += hi16(rv.x); y[2] += lo16(rv.y); y[3] += hi16(rv.y);
                 }
                 const int t = col / per_out, lc = col - t * per_out;
                 uint2 pk;
                 pk.x = pack2(y[0], y[1]);
                 pk.y = pack2(y[2], y[3]);
-                *reinterpret_cast<uint2*>(a.outs[t] + drow * per_out + lc) = pk;
+                *reinterpret_cast<uint2*>(a.outs[t] + drow[rb] * per_out + lc) = pk;
             }
         }
     }
