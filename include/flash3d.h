@@ -196,7 +196,7 @@ int f3d_bucket_swin_attn_bwd(const void *q, const void *k, const void *v, const 
  *   residual  NULL or bf16 [n, c_out], indexed by the DESTINATION row
  *   c_out     multiple of 64, at most 4096
  *   outs      HOST array of n_outs (1..4) DEVICE pointers: the c_out columns are split evenly over bf16 [n, c_out/n_outs]
- *             tensors (three for q, k, v); c_out / n_outs must be a multiple of 8
+ *             tensors (three for q, k, v); c_out / n_outs must be a multiple of 16
  *   row_out   NULL or [n] int32, a permutation: output row p is stored at row row_out[p]
  * Arithmetic: LayerNorm in fp32 on the bf16 input, rounded to bf16; bf16 MFMA with fp32 accumulation; bias and
  * residual added in fp32; one rounding to bf16.

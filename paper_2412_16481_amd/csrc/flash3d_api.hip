@@ -328,7 +328,7 @@ int f3d_ln_linear(const void* x, const int32_t* row_in, const float* gamma, cons
 {
     if (n < 0 || c_in < 1 || c_out < 1 || n_outs < 1 || !outs) return F3D_ERR_INVALID_ARG;
     if (n_outs > f3d::LIN_MAX_OUTS || (c_in != 64 && c_in != 128 && c_in != 256)) return F3D_ERR_UNSUPPORTED;
-    if (c_out % 64 != 0 || c_out % n_outs != 0 || (c_out / n_outs) % 8 != 0 || c_out > 4096) return F3D_ERR_UNSUPPORTED;
+    if (c_out % 64 != 0 || c_out % n_outs != 0 || (c_out / n_outs) % 16 != 0 || c_out > 4096) return F3D_ERR_UNSUPPORTED;
     if (n >= (int64_t)2147483647 - (1 << 20)) return F3D_ERR_UNSUPPORTED;
     if (gamma && !(eps >= 0.0f && isfinite(eps))) return F3D_ERR_INVALID_ARG;
     if (!gamma && beta) return F3D_ERR_INVALID_ARG;
