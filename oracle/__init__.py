@@ -41,6 +41,10 @@ def lib() -> ctypes.CDLL:
         _lib.orc_morton3.argtypes = [ctypes.c_uint32] * 3
         _lib.orc_hash.restype = ctypes.c_int64
         _lib.orc_bucketize.restype = ctypes.c_int64
+        _lib.orc_bucketize_ex.restype = ctypes.c_int64
+        _lib.orc_mix32.restype = ctypes.c_uint32
+        _lib.orc_mix32.argtypes = [ctypes.c_uint32]
+        _lib.orc_probe_direction.restype = ctypes.c_int32
         _lib.orc_group_of_bucket.restype = ctypes.c_int64
         _lib.orc_group_of_bucket.argtypes = [ctypes.c_int64] + [ctypes.c_int32] * 4
         _lib.orc_attn.restype = ctypes.c_int64
@@ -76,9 +80,17 @@ def group_of_bucket(j: int, m: int, mode: str, shift: int = 2, stride: int = 2) 
     return int(lib().orc_group_of_bucket(j, m, MODES[mode], shift, stride))
 
 
+ORDERS = {"index": 0, "canonical": 1}
+PROBE_MODES = {"axes": 0, "table": 1, "seeded": 2}
+
+
 def bucketize(coords: np.ndarray, batch_offsets: np.ndarray, voxel_size: float, bucket_size: int,
-              hash_name: str = "zorder_div", n_probes: int = 6, div: int = 0, probe_step: int = 0) -> Dict[str, np.ndarray]:
-    """Algorithms 1+2 under the round-synchronous, index-ordered schedule. Returns a dict with
+              hash_name: str = "zorder_div", n_probes: int = 6, div: int = 0, probe_step: int = 0,
+              order: str = "index", probe_mode: str = "axes", probe_seed: int = 0,
+              probe_table: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+    """Algorithms 1+2 under the round-synchronous schedule; contenders served by input index (order="index") or
+    by (Z-order code of the voxel, coordinates, index) (order="canonical"); probe offsets from the axis table, a
+    caller's table [n_probes, 3] of voxel offsets, or a seeded per-voxel draw. Returns a dict with
     bucket_id, bucket_off, round_of, perm, inv_perm, offsets[K+1], scan_bucket_start[n_scans+1]."""
     coords = np.ascontiguousarray(coords, dtype=np.float32).reshape(-1, 3)
     bo = np.ascontiguousarray(batch_offsets, dtype=np.int32)
@@ -87,16 +99,34 @@ def bucketize(coords: np.ndarray, batch_offsets: np.ndarray, voxel_size: float, 
     out = {k: np.full(n, -1, dtype=np.int32) for k in ("bucket_id", "bucket_off", "round_of", "perm", "inv_perm")}
     offsets = np.zeros(kmax + 1, dtype=np.int32)
     sbs = np.zeros(n_scans + 1, dtype=np.int32)
-    K = lib().orc_bucketize(_p(coords), _p(bo), ctypes.c_int64(n), ctypes.c_int32(n_scans),
-                            ctypes.c_float(voxel_size), ctypes.c_int32(bucket_size), ctypes.c_int32(HASHES[hash_name]),
-                            ctypes.c_int32(n_probes), ctypes.c_int32(div), ctypes.c_int32(probe_step),
-                            _p(out["bucket_id"]), _p(out["bucket_off"]), _p(out["round_of"]), _p(out["perm"]),
-                            _p(out["inv_perm"]), _p(offsets), _p(sbs))
+    tab = None
+    if probe_table is not None:
+        tab = np.zeros((6, 3), dtype=np.int32)
+        pt = np.asarray(probe_table, dtype=np.int32).reshape(-1, 3)
+        tab[: pt.shape[0]] = pt
+    K = lib().orc_bucketize_ex(_p(coords), _p(bo), ctypes.c_int64(n), ctypes.c_int32(n_scans),
+                               ctypes.c_float(voxel_size), ctypes.c_int32(bucket_size), ctypes.c_int32(HASHES[hash_name]),
+                               ctypes.c_int32(n_probes), ctypes.c_int32(div), ctypes.c_int32(probe_step),
+                               ctypes.c_int32(ORDERS[order]), ctypes.c_int32(PROBE_MODES[probe_mode]),
+                               ctypes.c_uint32(probe_seed & 0xFFFFFFFF), _p(tab),
+                               _p(out["bucket_id"]), _p(out["bucket_off"]), _p(out["round_of"]), _p(out["perm"]),
+                               _p(out["inv_perm"]), _p(offsets), _p(sbs))
     if K < 0:
-        raise ValueError("orc_bucketize: bad arguments")
+        raise ValueError("orc_bucketize_ex: bad arguments")
     out["offsets"] = offsets[: K + 1].copy()
     out["scan_bucket_start"] = sbs
     return out
+
+
+def mix32(x: int) -> int:
+    """The oracle's 32-bit mixer."""
+    return int(lib().orc_mix32(ctypes.c_uint32(x & 0xFFFFFFFF)))
+
+
+def probe_direction(seed: int, r: int, voxel) -> int:
+    """Direction 0..5 (+x, -x, +y, -y, +z, -z) of probe r for a point of this voxel under `seed`."""
+    v = np.ascontiguousarray(voxel, dtype=np.int32)
+    return int(lib().orc_probe_direction(ctypes.c_uint32(seed & 0xFFFFFFFF), ctypes.c_int32(r), _p(v)))
 
 
 def attn(q: np.ndarray, k: np.ndarray, v: np.ndarray, perm: Optional[np.ndarray], offsets: np.ndarray,

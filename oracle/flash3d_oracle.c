@@ -13,6 +13,9 @@
  *   - multi-head self-attention inside one scope         (Section 4.2; Appendix "Bucket-Swin")
  *   - gradient of that attention (plain definition)       (Section 4.2; the experiments report training latency)
  *   - in-bucket pooling: sub-bucket construction, reduce  (Section 4.2 "In-bucket Pooling"; Appendix "In-bucket Pooling")
+ *   - variants of the rebalancing (orc_bucketize_ex): contenders served in an order that does not depend on the input
+ *     order, probe offsets from a table or drawn per voxel from a seeded integer mixer
+ *     (Section 4.1 "Bucket rebalancing": the offsets are left open and called randomly perturbed)
  *
  * Algorithms 1 and 2 let hardware atomics decide the arrival order, so their result depends on
  * the schedule. The oracle fixes one admissible schedule: all points take the same step together
@@ -30,7 +33,10 @@
  * overflow-free inputs, brute-force masked dense attention, a library dense-attention routine on
  * the single-scope case, closed forms and invariants; for the pooling hand traces of the three steps, a
  * literal simulation with an AtomicInc primitive, capacity/coverage invariants, a brute-force
- * nearest-sub-bucket check and numpy reductions with an independent bf16 rounding. No function here is unpinned.
+ * nearest-sub-bucket check and numpy reductions with an independent bf16 rounding; for the rebalancing variants
+ * reductions to the pinned default (pre-sorted input, the axis table), equivariance under input permutation on
+ * overflowing inputs, a literal Python simulation, and bijectivity/avalanche/uniformity of the mixer. No function
+ * here is unpinned.
  */
 #include <math.h>
 #include <stdint.h>
@@ -131,6 +137,65 @@ int64_t orc_hash(int32_t hash, int64_t K, const int32_t vmax[3], int32_t div_ove
 
 /* ------------------------------------------------------------------ bucketize (Algorithms 1, 2) */
 
+/* ---- variants of the rebalancing -------------------------------------------------------------- */
+
+enum { ORC_ORDER_INDEX = 0, ORC_ORDER_CANONICAL = 1 };
+enum { ORC_PROBE_AXES = 0, ORC_PROBE_TABLE = 1, ORC_PROBE_SEEDED = 2 };
+
+/* A 32-bit integer mixer (xor-shift / odd multiply / xor-shift / odd multiply / xor-shift): a bijection of
+ * the 32-bit words with good avalanche. Used as a counter-based generator: no state, the same value on any
+ * machine for the same arguments. */
+uint32_t orc_mix32(uint32_t x)
+{
+    x ^= x >> 16;
+    x *= 0x7feb352du;
+    x ^= x >> 15;
+    x *= 0x846ca68bu;
+    x ^= x >> 16;
+    return x;
+}
+
+/* Direction (0..5, an index into ORC_PROBE_DIR) of probe r for a point of voxel v under `seed`: points of one
+ * voxel move together, and the draw does not depend on the point's index. */
+int32_t orc_probe_direction(uint32_t seed, int32_t r, const int32_t v[3])
+{
+    uint32_t h = orc_mix32(seed + (uint32_t)r);
+    h = orc_mix32(h ^ (uint32_t)v[0]);
+    h = orc_mix32(h ^ (uint32_t)v[1]);
+    h = orc_mix32(h ^ (uint32_t)v[2]);
+    return (int32_t)(((uint64_t)h * 6u) >> 32);
+}
+
+/* binary32 bit pattern mapped to an unsigned integer with the same order as the numbers (-0 below +0) */
+static uint32_t float_order_key(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, sizeof(u));
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+typedef struct {
+    uint64_t code;      /* Z-order code of the voxel */
+    uint32_t c[3];      /* ordered coordinate keys */
+    int64_t idx;        /* input index inside the scan */
+} orc_sort_rec;
+
+static int cmp_sort_rec(const void *pa, const void *pb)
+{
+    const orc_sort_rec *a = (const orc_sort_rec *)pa, *b = (const orc_sort_rec *)pb;
+    if (a->code != b->code) return a->code < b->code ? -1 : 1;
+    for (int k = 0; k < 3; ++k)
+        if (a->c[k] != b->c[k]) return a->c[k] < b->c[k] ? -1 : 1;
+    return a->idx < b->idx ? -1 : (a->idx > b->idx ? 1 : 0);
+}
+
+int64_t orc_bucketize_ex(const float *coords, const int32_t *batch_offsets, int64_t n, int32_t n_scans,
+                         float voxel_size, int32_t bucket_size, int32_t hash, int32_t n_probes,
+                         int32_t div_override, int32_t step_override,
+                         int32_t order, int32_t probe_mode, uint32_t probe_seed, const int32_t *probe_table,
+                         int32_t *bucket_id, int32_t *bucket_off, int32_t *round_of,
+                         int32_t *perm, int32_t *inv_perm, int32_t *offsets, int32_t *scan_bucket_start);
+
 /*
  * coords        [n,3] binary32, scans stored back to back
  * batch_offsets [n_scans+1], scan b owns points batch_offsets[b] .. batch_offsets[b+1]-1
@@ -151,8 +216,34 @@ int64_t orc_bucketize(const float *coords, const int32_t *batch_offsets, int64_t
                       int32_t *bucket_id, int32_t *bucket_off, int32_t *round_of,
                       int32_t *perm, int32_t *inv_perm, int32_t *offsets, int32_t *scan_bucket_start)
 {
+    return orc_bucketize_ex(coords, batch_offsets, n, n_scans, voxel_size, bucket_size, hash, n_probes, div_override,
+                            step_override, ORC_ORDER_INDEX, ORC_PROBE_AXES, 0u, NULL, bucket_id, bucket_off, round_of,
+                            perm, inv_perm, offsets, scan_bucket_start);
+}
+
+/*
+ * The same schedule with two choices opened up (Section 4.1 "Bucket rebalancing" leaves both to the hardware race
+ * and to "each probe offset"):
+ *   order        ORC_ORDER_INDEX: contenders are served in increasing input index.
+ *                ORC_ORDER_CANONICAL: in increasing (Z-order code of the voxel, x, y, z as numbers, input index),
+ *                so that the partition of the POINTS does not depend on the order in which they are stored
+ *                (only points with identical coordinates can still swap places).
+ *   probe_mode   ORC_PROBE_AXES: probe r moves the voxel to the r-th axis neighbour at distance `step`.
+ *                ORC_PROBE_TABLE: probe r adds probe_table[3(r-1) .. 3(r-1)+2] voxels (the caller draws them).
+ *                ORC_PROBE_SEEDED: probe r moves the voxel by `step` in direction orc_probe_direction(seed, r, v).
+ * In every mode the moved voxel is clamped to the scan's voxel box.
+ */
+int64_t orc_bucketize_ex(const float *coords, const int32_t *batch_offsets, int64_t n, int32_t n_scans,
+                         float voxel_size, int32_t bucket_size, int32_t hash, int32_t n_probes,
+                         int32_t div_override, int32_t step_override,
+                         int32_t order, int32_t probe_mode, uint32_t probe_seed, const int32_t *probe_table,
+                         int32_t *bucket_id, int32_t *bucket_off, int32_t *round_of,
+                         int32_t *perm, int32_t *inv_perm, int32_t *offsets, int32_t *scan_bucket_start)
+{
     if (n < 0 || n_scans < 0 || !(voxel_size > 0.0f) || bucket_size <= 0 || hash < 0 || hash > 3 ||
         n_probes < 0 || n_probes > 6 || !perm)
+        return -1;
+    if (order < 0 || order > 1 || probe_mode < 0 || probe_mode > 2 || (probe_mode == ORC_PROBE_TABLE && !probe_table))
         return -1;
     const float inv = 1.0f / voxel_size;
     int64_t kbase = 0; /* buckets of earlier scans */
@@ -195,8 +286,24 @@ int64_t orc_bucketize(const float *coords, const int32_t *batch_offsets, int64_t
         cap[K - 1] = nb - (K - 1) * (int64_t)bucket_size;
         int8_t *placed = (int8_t *)calloc((size_t)nb, 1);
 
+        /* the order in which the points of the scan are served inside every step */
+        int64_t *ord = (int64_t *)malloc(sizeof(int64_t) * (size_t)nb);
+        for (int64_t i = 0; i < nb; ++i) ord[i] = i;
+        if (order == ORC_ORDER_CANONICAL) {
+            orc_sort_rec *rec = (orc_sort_rec *)malloc(sizeof(orc_sort_rec) * (size_t)nb);
+            for (int64_t i = 0; i < nb; ++i) {
+                rec[i].code = orc_morton3((uint32_t)v[3 * i], (uint32_t)v[3 * i + 1], (uint32_t)v[3 * i + 2]);
+                for (int a = 0; a < 3; ++a) rec[i].c[a] = float_order_key(coords[3 * (p0 + i) + a]);
+                rec[i].idx = i;
+            }
+            qsort(rec, (size_t)nb, sizeof(orc_sort_rec), cmp_sort_rec);
+            for (int64_t i = 0; i < nb; ++i) ord[i] = rec[i].idx;
+            free(rec);
+        }
+
         /* step 0: direct hash (Algorithm 1, lines 5-9) */
-        for (int64_t i = 0; i < nb; ++i) {
+        for (int64_t t = 0; t < nb; ++t) {
+            const int64_t i = ord[t];
             int64_t j = hash_bucket(&cfg, &v[3 * i]);
             if (cnt[j] < cap[j]) {
                 id[p0 + i] = (int32_t)j;
@@ -207,14 +314,18 @@ int64_t orc_bucketize(const float *coords, const int32_t *batch_offsets, int64_t
         }
         /* steps 1..n_probes: Algorithm 2, one probe offset per step */
         for (int32_t r = 1; r <= n_probes; ++r) {
-            for (int64_t i = 0; i < nb; ++i) {
+            for (int64_t t = 0; t < nb; ++t) {
+                const int64_t i = ord[t];
                 if (placed[i]) continue;
                 int32_t w[3];
+                const int32_t dir = probe_mode == ORC_PROBE_SEEDED ? orc_probe_direction(probe_seed, r, &v[3 * i]) : r - 1;
                 for (int a = 0; a < 3; ++a) {
-                    int64_t t = (int64_t)v[3 * i + a] + (int64_t)ORC_PROBE_DIR[r - 1][a] * cfg.step;
-                    if (t < 0) t = 0;
-                    if (t > vmax[a]) t = vmax[a];
-                    w[a] = (int32_t)t;
+                    const int64_t delta = probe_mode == ORC_PROBE_TABLE ? (int64_t)probe_table[3 * (r - 1) + a]
+                                                                        : (int64_t)ORC_PROBE_DIR[dir][a] * cfg.step;
+                    int64_t moved = (int64_t)v[3 * i + a] + delta;
+                    if (moved < 0) moved = 0;
+                    if (moved > vmax[a]) moved = vmax[a];
+                    w[a] = (int32_t)moved;
                 }
                 int64_t j = hash_bucket(&cfg, w);
                 if (cnt[j] < cap[j]) {
@@ -227,7 +338,8 @@ int64_t orc_bucketize(const float *coords, const int32_t *batch_offsets, int64_t
         }
         /* recycle (Algorithm 2, lines 19-22): leftovers fill the free slots, first bucket first */
         int64_t j = 0;
-        for (int64_t i = 0; i < nb; ++i) {
+        for (int64_t t = 0; t < nb; ++t) {
+            const int64_t i = ord[t];
             if (placed[i]) continue;
             while (cnt[j] >= cap[j]) ++j;
             id[p0 + i] = (int32_t)j;
@@ -254,7 +366,7 @@ int64_t orc_bucketize(const float *coords, const int32_t *batch_offsets, int64_t
             if (bucket_id) bucket_id[i] = (int32_t)(kbase + id[i]);
             if (bucket_off) bucket_off[i] = off[i];
         }
-        free(base); free(placed); free(cap); free(cnt); free(v);
+        free(base); free(placed); free(cap); free(cnt); free(v); free(ord);
         kbase += K;
     }
     if (scan_bucket_start) scan_bucket_start[n_scans] = (int32_t)kbase;
