@@ -58,7 +58,25 @@ extern "C" {
 #define F3D_SCHEDULE_GENERAL 1 /* two launches per step, any size                                      */
 #define F3D_SCHEDULE_STEPS 2   /* one launch per step                                                  */
 
-#define F3D_MAX_PROBES 6          /* probe offsets of Algorithm 2: the six axis neighbours           */
+/* Variants of the rebalancing (Section 4.1 "Bucket rebalancing": Algorithm 2 leaves the arrival order of the
+ * contenders of a bucket to the hardware race, and the probe offsets open, calling them randomly perturbed).
+ * F3D_ORDER_INDEX serves the contenders of a bucket in increasing input index. F3D_ORDER_CANONICAL serves them in
+ * increasing (Z-order code of the voxel, x, y, z as numbers, input index): the partition of the POINTS then does
+ * not depend on the order in which they are stored (only points with identical coordinates can swap rows); it
+ * costs a sort of the points before the bucketing. */
+#define F3D_ORDER_INDEX 0
+#define F3D_ORDER_CANONICAL 1
+/* Probe r (1..n_probes) moves the voxel of a point that is still unplaced, clamped to the scan's voxel box:
+ * AXES   to the r-th of the six axis neighbours (+x, -x, +y, -y, +z, -z) at distance probe_step;
+ * TABLE  by probe_table[r-1] voxels (the caller draws the offsets, e.g. from a seeded generator);
+ * SEEDED by probe_step along the axis direction number (h * 6) >> 32, where h = mix(mix(mix(mix(seed + r) ^ vx)
+ *        ^ vy) ^ vz) over the point's voxel and mix(x) is: x ^= x >> 16; x *= 0x7feb352d; x ^= x >> 15;
+ *        x *= 0x846ca68b; x ^= x >> 16 (32-bit arithmetic). Points of one voxel move together. */
+#define F3D_PROBE_AXES 0
+#define F3D_PROBE_TABLE 1
+#define F3D_PROBE_SEEDED 2
+
+#define F3D_MAX_PROBES 6          /* probe offsets of Algorithm 2                                      */
 #define F3D_MAX_SCAN_BUCKETS 8192 /* most hash buckets one scan may own                               */
 #define F3D_MAX_SCOPE_BUCKETS 16  /* most buckets per attention scope                                 */
 #define F3D_MAX_VOXEL ((1 << 21) - 1) /* voxel coordinates saturate here (63-bit Morton code)        */
@@ -76,10 +94,14 @@ typedef struct f3d_params {
     int64_t max_scan_points; /* upper bound on the points of any one scan; 0 = n. Sizes the workspace and    */
                              /* must satisfy ceil(max_scan_points / S) <= F3D_MAX_SCAN_BUCKETS               */
     int32_t schedule;        /* F3D_SCHEDULE_*; 0 = automatic                                                */
-    int32_t reserved;        /* 0                                                                            */
+    int32_t order;           /* F3D_ORDER_*                                                                  */
+    int32_t probe_mode;      /* F3D_PROBE_*                                                                  */
+    uint32_t probe_seed;     /* seed of F3D_PROBE_SEEDED                                                     */
+    int32_t probe_table[3 * F3D_MAX_PROBES]; /* voxel offsets (x, y, z) of probes 1..6 for F3D_PROBE_TABLE   */
 } f3d_params;
 
-/* Fill *p with the defaults: scope_buckets 4, Z-order-div hash, 6 probes, automatic divisor and step. */
+/* Fill *p with the defaults: scope_buckets 4, Z-order-div hash, 6 axis probes, automatic divisor and step,
+ * contenders served by input index. */
 void f3d_params_default(f3d_params *p, float voxel_size, int32_t bucket_cap);
 
 /* Upper bound on the total number of hash buckets: n / S + n_scans. `offsets` needs this many + 1 ints. */
@@ -92,7 +114,8 @@ int f3d_workspace_bytes(int64_t n, int32_t n_scans, const f3d_params *p, size_t 
  * PSH bucketing with rebalancing (Algorithms 1 and 2; Appendix "PSH with Two-Stage Counters").
  * The racing atomics of the paper are replaced by a deterministic schedule with the same
  * admissible result: all points take the same step together (direct hash, then probe 1, ...), and
- * the points contending for a bucket in one step are served in increasing input index.
+ * the points contending for a bucket in one step are served in increasing input index (or in the canonical
+ * order, see F3D_ORDER_CANONICAL; perm and inv_perm always refer to the caller's indices).
  *
  *   coords            [n,3] binary32, 4-byte aligned, scans stored back to back
  *   batch_offsets     [n_scans+1] int32, non-decreasing, first 0, last n; NULL = one scan of n points

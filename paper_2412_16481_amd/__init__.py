@@ -19,6 +19,8 @@ ERR_INVALID_ARG, ERR_BAD_ALIGNMENT, ERR_WORKSPACE_TOO_SMALL, ERR_UNSUPPORTED, ER
 HASHES = {"xor_mod": 0, "xor_div": 1, "zorder_mod": 2, "zorder_div": 3}
 MODES = {"plain": 0, "shift": 1, "stride": 2}
 SCHEDULES = {"auto": 0, "general": 1, "steps": 2}
+ORDERS = {"index": 0, "canonical": 1}
+PROBE_MODES = {"axes": 0, "table": 1, "seeded": 2}
 
 EXPORTS = ("f3d_params_default", "f3d_max_buckets", "f3d_workspace_bytes", "f3d_psh_bucketize",
            "f3d_bucket_swin_attn", "f3d_attn_bwd_workspace_bytes", "f3d_bucket_swin_attn_bwd", "f3d_ln_linear", "f3d_pool_max_rows", "f3d_pool_workspace_bytes", "f3d_inbucket_pool",
@@ -30,7 +32,8 @@ class f3d_params(ctypes.Structure):
     _fields_ = [("struct_size", ctypes.c_uint32), ("voxel_size", ctypes.c_float), ("bucket_cap", ctypes.c_int32),
                 ("scope_buckets", ctypes.c_int32), ("hash", ctypes.c_int32), ("n_probes", ctypes.c_int32),
                 ("div", ctypes.c_int32), ("probe_step", ctypes.c_int32), ("max_scan_points", ctypes.c_int64),
-                ("schedule", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("schedule", ctypes.c_int32), ("order", ctypes.c_int32), ("probe_mode", ctypes.c_int32),
+                ("probe_seed", ctypes.c_uint32), ("probe_table", ctypes.c_int32 * 18)]
 
 
 class Flash3DError(RuntimeError):
@@ -101,7 +104,9 @@ def version() -> int:
 
 def make_params(voxel_size: float, bucket_cap: int, scope_buckets: int = 4, hash: str = "zorder_div",
                 n_probes: int = 6, div: int = 0, probe_step: int = 0, max_scan_points: int = 0,
-                schedule: str = "auto") -> f3d_params:
+                schedule: str = "auto", order: str = "index", probe_mode: str = "axes", probe_seed: int = 0,
+                probe_table=None) -> f3d_params:
+    """f3d_params with the defaults of f3d_params_default. probe_table: up to 6 rows of 3 voxel offsets (ints)."""
     p = f3d_params()
     lib().f3d_params_default(ctypes.byref(p), voxel_size, bucket_cap)
     p.scope_buckets = scope_buckets
@@ -111,6 +116,15 @@ def make_params(voxel_size: float, bucket_cap: int, scope_buckets: int = 4, hash
     p.probe_step = probe_step
     p.max_scan_points = max_scan_points
     p.schedule = SCHEDULES[schedule] if isinstance(schedule, str) else int(schedule)
+    p.order = ORDERS[order] if isinstance(order, str) else int(order)
+    p.probe_mode = PROBE_MODES[probe_mode] if isinstance(probe_mode, str) else int(probe_mode)
+    p.probe_seed = int(probe_seed) & 0xFFFFFFFF
+    if probe_table is not None:
+        flat = [int(x) for row in probe_table for x in row]
+        if len(flat) > 18:
+            raise ValueError("probe_table holds at most 6 offsets")
+        for i, x in enumerate(flat):
+            p.probe_table[i] = x
     return p
 
 

@@ -9,6 +9,7 @@
 #include "flash3d.h"
 #include "linear.h"
 #include "pool.h"
+#include "order.h"
 #include "psh.h"
 
 namespace {
@@ -32,6 +33,8 @@ struct Plan {
     size_t bytes;
     // offsets (bytes) of the workspace arrays
     size_t o_status, o_p0, o_c0, o_mm, o_cnt, o_cnt2, o_hist, o_key, o_left, o_leftpre, o_freepre, o_inv, o_rc, o_cfg, o_done, o_ci;
+    // canonical order only
+    size_t o_obox, o_owords, o_oidx0, o_oidx1, o_ohist, o_ocoords, o_operm;
 };
 
 int check_params(int64_t n, int32_t n_scans, const f3d_params* p)
@@ -43,7 +46,9 @@ int check_params(int64_t n, int32_t n_scans, const f3d_params* p)
     if (p->hash < 0 || p->hash > 3) return F3D_ERR_INVALID_ARG;
     if (p->n_probes < 0 || p->n_probes > F3D_MAX_PROBES) return F3D_ERR_INVALID_ARG;
     if (p->div < 0 || p->probe_step < 0 || p->max_scan_points < 0) return F3D_ERR_INVALID_ARG;
-    if (p->schedule < F3D_SCHEDULE_AUTO || p->schedule > F3D_SCHEDULE_STEPS || p->reserved != 0) return F3D_ERR_INVALID_ARG;
+    if (p->schedule < F3D_SCHEDULE_AUTO || p->schedule > F3D_SCHEDULE_STEPS) return F3D_ERR_INVALID_ARG;
+    if (p->order < F3D_ORDER_INDEX || p->order > F3D_ORDER_CANONICAL) return F3D_ERR_INVALID_ARG;
+    if (p->probe_mode < F3D_PROBE_AXES || p->probe_mode > F3D_PROBE_SEEDED) return F3D_ERR_INVALID_ARG;
     if (p->bucket_cap % (16 * p->scope_buckets) != 0) return F3D_ERR_INVALID_ARG;
     if (p->scope_buckets > F3D_MAX_SCOPE_BUCKETS) return F3D_ERR_UNSUPPORTED;
     if (n >= (int64_t)2147483647 - (1 << 20)) return F3D_ERR_UNSUPPORTED;
@@ -88,6 +93,15 @@ void make_plan(int64_t n, int32_t n_scans, const f3d_params* p, Plan* pl)
     }
     pl->o_key = take((size_t)n * 4);
     pl->o_inv = take((size_t)n * 4);
+    if (p->order == F3D_ORDER_CANONICAL) {
+        pl->o_obox = take((size_t)n_scans * 16);
+        pl->o_owords = take((size_t)n * 24);
+        pl->o_oidx0 = take((size_t)n * 4);
+        pl->o_oidx1 = take((size_t)n * 4);
+        pl->o_ohist = take(f3d::order_hist_bytes(n));
+        pl->o_ocoords = take((size_t)n * 12);
+        pl->o_operm = take((size_t)n * 4);
+    }
     pl->bytes = at;
 }
 
@@ -175,6 +189,9 @@ int f3d_psh_bucketize(const float* coords, const int32_t* batch_offsets, int64_t
     a.n_probes = p->n_probes;
     a.div = p->div;
     a.step = p->probe_step;
+    a.probe_mode = p->probe_mode;
+    a.probe_seed = p->probe_seed;
+    for (int i = 0; i < 3 * F3D_MAX_PROBES; ++i) a.probe_table[i] = p->probe_table[i];
     a.kcap = pl.kcap;
     a.max_scan_points = pl.max_scan_points;
     a.max_buckets = (int)pl.max_buckets;
@@ -202,8 +219,32 @@ int f3d_psh_bucketize(const float* coords, const int32_t* batch_offsets, int64_t
     int schedule = p->schedule;
     if (schedule == F3D_SCHEDULE_AUTO) schedule = fast_ok ? F3D_SCHEDULE_STEPS : F3D_SCHEDULE_GENERAL;
     if (schedule == F3D_SCHEDULE_STEPS && !fast_ok) return F3D_ERR_UNSUPPORTED;
-    const hipError_t e = schedule == F3D_SCHEDULE_GENERAL ? f3d::psh_launch(a, (hipStream_t)stream)
-                                                          : f3d::psh_fast_launch(a, (hipStream_t)stream);
+    // canonical order: sort the points, bucket the sorted copy by index, map the result back through the sort
+    const int32_t* order = nullptr;
+    if (p->order == F3D_ORDER_CANONICAL) {
+        f3d::OrderArgs o;
+        memset(&o, 0, sizeof(o));
+        o.coords = coords;
+        o.batch_offsets = batch_offsets;
+        o.n = (int)n;
+        o.n_scans = n_scans;
+        o.inv_voxel = a.inv_voxel;
+        o.box = (uint32_t*)(ws + pl.o_obox);
+        o.words = (uint32_t*)(ws + pl.o_owords);
+        o.idx[0] = (int32_t*)(ws + pl.o_oidx0);
+        o.idx[1] = (int32_t*)(ws + pl.o_oidx1);
+        o.hist = (uint32_t*)(ws + pl.o_ohist);
+        o.coords_sorted = (float*)(ws + pl.o_ocoords);
+        const hipError_t eo = f3d::order_launch(o, &order, (hipStream_t)stream);
+        if (eo != hipSuccess) return hip_fail(eo);
+        a.coords = o.coords_sorted;
+        a.perm = (int32_t*)(ws + pl.o_operm);
+        a.inv_perm = (int32_t*)(ws + pl.o_inv);
+    }
+    hipError_t e = schedule == F3D_SCHEDULE_GENERAL ? f3d::psh_launch(a, (hipStream_t)stream)
+                                                    : f3d::psh_fast_launch(a, (hipStream_t)stream);
+    if (e == hipSuccess && order)
+        e = f3d::order_compose_launch(order, a.perm, a.inv_perm, (int)n, a.status, perm, inv_perm, (hipStream_t)stream);
     return e == hipSuccess ? F3D_OK : hip_fail(e);
 }
 

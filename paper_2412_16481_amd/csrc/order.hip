@@ -1,0 +1,260 @@
+// Canonical serving order for the rebalancing of Algorithm 2 (Section 4.1 "Bucket rebalancing" leaves the arrival
+// order of the contenders of a bucket to the hardware race). Serving them in increasing
+// (Z-order code of the voxel, x, y, z, input index) makes the partition of the points independent of the order in
+// which they are stored. It is done by sorting the points once by that key and running the index-ordered bucketing on
+// the sorted copy; the result is mapped back through the sort order.
+//
+// The sort is a stable least-significant-digit radix sort on 8-bit digits of six 32-bit key words per point, carrying
+// only the point index: per pass one kernel counts the digits of every tile of 2048 positions, and one kernel sums the
+// count rows of the earlier tiles itself (no separate scan launch), ranks its tile by digit in position order (wave
+// ballots over the digit's bits plus per-(round, wave) counters in LDS) and scatters the indices.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "order.h"
+#include "psh.h"
+#include "psh_common.h"
+
+namespace f3d {
+namespace {
+
+constexpr int OT = 256;          // threads per workgroup
+constexpr int OE = 2048;         // positions per tile
+constexpr int OR = OE / OT;      // rounds: position = tile*OE + round*OT + thread
+constexpr int OW = OT / 64;      // waves
+
+__device__ __forceinline__ int scan_of(const OrderArgs& a, int p)
+{
+    return a.batch_offsets ? find_scan(a.batch_offsets, a.n_scans, p) : 0;
+}
+
+__global__ __launch_bounds__(OT) void k_order_init(OrderArgs a)
+{
+    const int i = blockIdx.x * OT + threadIdx.x;
+    if (i < a.n_scans * 4) a.box[i] = 0xFFFFFFFFu;
+}
+
+// per-scan coordinate minimum (Algorithm 1, "compute voxel coordinate")
+__global__ __launch_bounds__(OT) void k_order_box(OrderArgs a)
+{
+    const int lane = threadIdx.x & 63;
+    int cur = -1;
+    uint32_t mn[3] = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
+    const auto flush = [&]() {
+        // every lane of the wave arrives here together; lanes with cur < 0 have nothing to give
+        const unsigned long long have = __ballot(cur >= 0);
+        if (!have) return;
+        const int first = __shfl(cur, __ffsll((long long)have) - 1, 64);
+        const bool uniform = __ballot(cur >= 0 && cur != first) == 0;
+        if (uniform) {
+#pragma unroll
+            for (int t = 0; t < 3; ++t) {
+                uint32_t lo = mn[t];
+                for (int d = 32; d >= 1; d >>= 1) lo = min(lo, (uint32_t)__shfl_xor((int)lo, d, 64));
+                if (lane == 0) atomicMin(&a.box[first * 4 + t], lo);
+            }
+        } else if (cur >= 0) {
+#pragma unroll
+            for (int t = 0; t < 3; ++t) atomicMin(&a.box[cur * 4 + t], mn[t]);
+        }
+    };
+#pragma unroll 1
+    for (int r = 0; r < OR; ++r) {
+        const long long e = (long long)blockIdx.x * OE + r * OT + threadIdx.x;
+        const bool ok = e < a.n;
+        const int b = ok ? scan_of(a, (int)e) : -1;
+        // a wave changes scan together or not at all in the common case; any lane that changes flushes the whole wave
+        if (__ballot(ok && cur >= 0 && b != cur)) {
+            flush();
+            cur = -1;
+            mn[0] = mn[1] = mn[2] = 0xFFFFFFFFu;
+        }
+        if (ok) {
+            cur = b;
+#pragma unroll
+            for (int t = 0; t < 3; ++t) mn[t] = min(mn[t], f2ord(a.coords[(size_t)e * 3 + t]));
+        }
+    }
+    flush();
+}
+
+// key words of every point
+__global__ __launch_bounds__(OT) void k_order_keys(OrderArgs a)
+{
+    const long long p = (long long)blockIdx.x * OT + threadIdx.x;
+    if (p >= a.n) return;
+    const int b = scan_of(a, (int)p);
+    int v[3];
+    uint32_t o[3];
+#pragma unroll
+    for (int t = 0; t < 3; ++t) {
+        const float c = a.coords[(size_t)p * 3 + t];
+        o[t] = f2ord(c);
+        v[t] = voxel_of(c, ord2f(a.box[b * 4 + t]), a.inv_voxel);
+    }
+    const uint64_t code = morton3(v[0], v[1], v[2]);
+    const size_t n = (size_t)a.n;
+    a.words[0 * n + p] = o[2];
+    a.words[1 * n + p] = o[1];
+    a.words[2 * n + p] = o[0];
+    a.words[3 * n + p] = (uint32_t)code;
+    a.words[4 * n + p] = (uint32_t)(code >> 32);
+    a.words[5 * n + p] = (uint32_t)b;
+}
+
+__global__ __launch_bounds__(OT) void k_order_count(const int32_t* __restrict__ src, const uint32_t* __restrict__ word, int shift,
+                                                    int n, uint32_t* __restrict__ hist)
+{
+    __shared__ uint32_t h[256];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < OR; ++r) {
+        const long long e = (long long)blockIdx.x * OE + r * OT + threadIdx.x;
+        if (e < n) {
+            const int i = src ? src[e] : (int)e;
+            atomicAdd(&h[(word[i] >> shift) & 255u], 1u);
+        }
+    }
+    __syncthreads();
+    hist[(size_t)blockIdx.x * 256 + threadIdx.x] = h[threadIdx.x];
+}
+
+__global__ __launch_bounds__(OT) void k_order_scatter(const int32_t* __restrict__ src, int32_t* __restrict__ dst,
+                                                      const uint32_t* __restrict__ word, int shift, int n,
+                                                      const uint32_t* __restrict__ hist, int tiles)
+{
+    __shared__ uint32_t base[256];
+    __shared__ uint32_t wsum[OW];
+    __shared__ uint16_t cnt[OR * OW][256];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tile = blockIdx.x;
+
+    // first position of digit `tid` for this tile: all smaller digits of all tiles, plus this digit in earlier tiles
+    uint32_t pre = 0, tot = 0;
+#pragma unroll 8
+    for (int t = 0; t < tiles; ++t) {
+        const uint32_t c = hist[(size_t)t * 256 + tid];
+        pre += t < tile ? c : 0u;
+        tot += c;
+    }
+    uint32_t inc = tot;
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = (uint32_t)__shfl_up((int)inc, d, 64);
+        if (lane >= d) inc += o;
+    }
+    if (lane == 63) wsum[wave] = inc;
+    uint32_t* cz = reinterpret_cast<uint32_t*>(&cnt[0][0]);
+#pragma unroll
+    for (int j = 0; j < OR * OW * 256 / 2 / OT; ++j) cz[j * OT + tid] = 0u;
+    __syncthreads();
+    uint32_t before = 0;
+    for (int w = 0; w < wave; ++w) before += wsum[w];
+    base[tid] = before + inc - tot + pre;
+
+    // digit of every position of the tile and its rank among equal digits of the same wave and round
+    int idx[OR], dig[OR], rk[OR];
+#pragma unroll
+    for (int r = 0; r < OR; ++r) {
+        const long long e = (long long)tile * OE + r * OT + tid;
+        const bool ok = e < n;
+        idx[r] = ok ? (src ? src[e] : (int)e) : 0;
+        dig[r] = ok ? (int)((word[idx[r]] >> shift) & 255u) : -1;
+    }
+#pragma unroll
+    for (int r = 0; r < OR; ++r) {
+        const bool ok = dig[r] >= 0;
+        unsigned long long peers = __ballot(ok);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const unsigned long long bal = __ballot(ok && ((dig[r] >> b) & 1));
+            peers &= ((dig[r] >> b) & 1) ? bal : ~bal;
+        }
+        rk[r] = __popcll(peers & ((1ull << lane) - 1ull));
+        if (ok && rk[r] == 0) cnt[r * OW + wave][dig[r]] = (uint16_t)__popcll(peers);
+    }
+    __syncthreads();
+    {   // exclusive prefix over the (round, wave) rows, one digit per thread
+        uint32_t run = 0;
+#pragma unroll
+        for (int row = 0; row < OR * OW; ++row) {
+            const uint32_t c = cnt[row][tid];
+            cnt[row][tid] = (uint16_t)run;
+            run += c;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < OR; ++r) {
+        if (dig[r] < 0) continue;
+        const uint32_t pos = base[dig[r]] + cnt[r * OW + wave][dig[r]] + (uint32_t)rk[r];
+        if (pos < (uint32_t)n) dst[pos] = idx[r];
+    }
+}
+
+__global__ __launch_bounds__(OT) void k_order_gather(const int32_t* __restrict__ order, const float* __restrict__ coords, int n,
+                                                     float* __restrict__ out)
+{
+    const long long p = (long long)blockIdx.x * OT + threadIdx.x;
+    if (p >= n) return;
+    const unsigned i = (unsigned)order[p];
+    if (i >= (unsigned)n) return;
+    out[(size_t)p * 3 + 0] = coords[(size_t)i * 3 + 0];
+    out[(size_t)p * 3 + 1] = coords[(size_t)i * 3 + 1];
+    out[(size_t)p * 3 + 2] = coords[(size_t)i * 3 + 2];
+}
+
+__global__ __launch_bounds__(OT) void k_order_compose(const int32_t* __restrict__ order, const int32_t* __restrict__ perm_sorted,
+                                                      const int32_t* __restrict__ inv_sorted, int n, const int32_t* __restrict__ status,
+                                                      int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm)
+{
+    if (status[0]) return;
+    const long long p = (long long)blockIdx.x * OT + threadIdx.x;
+    if (p >= n) return;
+    const unsigned s = (unsigned)perm_sorted[p];
+    if (s < (unsigned)n) perm[p] = order[s];
+    const unsigned i = (unsigned)order[p];
+    if (inv_perm && i < (unsigned)n) inv_perm[i] = inv_sorted[p];
+}
+
+}  // namespace
+
+size_t order_hist_bytes(long long n) { return (size_t)((n + OE - 1) / OE + 1) * 256 * 4; }
+
+hipError_t order_launch(const OrderArgs& a, const int32_t** order_out, hipStream_t stream)
+{
+    *order_out = a.idx[0];
+    if (a.n <= 0) return hipSuccess;
+    const int tiles = (a.n + OE - 1) / OE;
+    const int blocks = (a.n + OT - 1) / OT;
+    k_order_init<<<(a.n_scans * 4 + OT - 1) / OT, OT, 0, stream>>>(a);
+    k_order_box<<<tiles, OT, 0, stream>>>(a);
+    k_order_keys<<<blocks, OT, 0, stream>>>(a);
+    // least significant first: z, y, x, the code's low and high word (31 bits), the scan (as many digits as it needs)
+    const int32_t* src = nullptr;
+    int cur = 0;
+    const int scan_digits = a.n_scans > 256 ? 2 : (a.n_scans > 1 ? 1 : 0);
+    for (int w = 0; w < 6; ++w) {
+        const int digits = w < 5 ? 4 : scan_digits;
+        const uint32_t* word = a.words + (size_t)w * a.n;
+        for (int d = 0; d < digits; ++d) {
+            k_order_count<<<tiles, OT, 0, stream>>>(src, word, 8 * d, a.n, a.hist);
+            k_order_scatter<<<tiles, OT, 0, stream>>>(src, a.idx[cur], word, 8 * d, a.n, a.hist, tiles);
+            src = a.idx[cur];
+            cur ^= 1;
+        }
+    }
+    *order_out = src;
+    k_order_gather<<<blocks, OT, 0, stream>>>(src, a.coords, a.n, a.coords_sorted);
+    return hipGetLastError();
+}
+
+hipError_t order_compose_launch(const int32_t* order, const int32_t* perm_sorted, const int32_t* inv_sorted, int n,
+                                const int32_t* status, int32_t* perm, int32_t* inv_perm, hipStream_t stream)
+{
+    if (n <= 0) return hipSuccess;
+    k_order_compose<<<(n + OT - 1) / OT, OT, 0, stream>>>(order, perm_sorted, inv_sorted, n, status, perm, inv_perm);
+    return hipGetLastError();
+}
+
+}  // namespace f3d

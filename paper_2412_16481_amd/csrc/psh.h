@@ -22,6 +22,9 @@ struct PshArgs {
     int n_probes;
     int div;
     int step;
+    int probe_mode;          // 0 axis neighbours, 1 table, 2 seeded per-voxel direction
+    uint32_t probe_seed;
+    int probe_table[18];     // [6][3] voxel offsets of mode 1
     int kcap;    // pitch of the count matrix = most buckets a scan may have
     int chunk;   // points per workgroup chunk
     long long max_scan_points;

@@ -201,7 +201,7 @@ __global__ __launch_bounds__(PSH_THREADS) void k_psh_step(PshArgs a, int r)
             int x = voxel_of(c[0], cfg.mn[0], a.inv_voxel);
             int y = voxel_of(c[1], cfg.mn[1], a.inv_voxel);
             int z = voxel_of(c[2], cfg.mn[2], a.inv_voxel);
-            if (r > 0) probe_voxel(r, cfg, x, y, z);
+            if (r > 0) probe_voxel(a, r, cfg, x, y, z);
             h = hash_bucket(a.hash, x, y, z, cfg);
         }
         // lanes of this wave that contend for the same bucket, by ballots over the key bits

@@ -127,14 +127,46 @@ __device__ __forceinline__ int hash_bucket(int hash, int x, int y, int z, const 
     return (int)(q < (long long)c.K ? q : (long long)(c.K - 1));
 }
 
-// voxel of a point moved by probe r (1..6): +-step along x, y, z in that order, clamped to the scan's voxel box
-__device__ __forceinline__ void probe_voxel(int r, const ScanCfg& c, int& x, int& y, int& z)
+// 32-bit mixer (xor-shift, odd multiply, xor-shift, odd multiply, xor-shift): a stateless generator for the seeded
+// probe directions; any machine computes the same value from the same arguments
+__device__ __forceinline__ uint32_t mix32(uint32_t x)
 {
-    const int ax = (r - 1) >> 1;
-    const long long d = ((r - 1) & 1) ? -(long long)c.step : (long long)c.step;
-    if (ax == 0) x = (int)min(max((long long)x + d, 0ll), (long long)c.vmax[0]);
-    if (ax == 1) y = (int)min(max((long long)y + d, 0ll), (long long)c.vmax[1]);
-    if (ax == 2) z = (int)min(max((long long)z + d, 0ll), (long long)c.vmax[2]);
+    x ^= x >> 16;
+    x *= 0x7feb352du;
+    x ^= x >> 15;
+    x *= 0x846ca68bu;
+    x ^= x >> 16;
+    return x;
+}
+
+// voxel of a point moved by probe r (1..6), clamped to the scan's voxel box (Algorithm 2, "perturb voxel coordinate").
+// mode 0: +-step along x, y, z in that order; mode 1: the caller's table of voxel offsets; mode 2: +-step along an
+// axis drawn from (seed, r, voxel), so that the points of a voxel move together whatever their indices are.
+__device__ __forceinline__ void probe_voxel(const PshArgs& a, int r, const ScanCfg& c, int& x, int& y, int& z)
+{
+    long long dx = 0, dy = 0, dz = 0;
+    if (a.probe_mode == 1) {
+        dx = a.probe_table[3 * (r - 1)];
+        dy = a.probe_table[3 * (r - 1) + 1];
+        dz = a.probe_table[3 * (r - 1) + 2];
+    } else {
+        int dir = r - 1;
+        if (a.probe_mode == 2) {
+            uint32_t h = mix32(a.probe_seed + (uint32_t)r);
+            h = mix32(h ^ (uint32_t)x);
+            h = mix32(h ^ (uint32_t)y);
+            h = mix32(h ^ (uint32_t)z);
+            dir = (int)(((unsigned long long)h * 6ull) >> 32);
+        }
+        const long long d = (dir & 1) ? -(long long)c.step : (long long)c.step;
+        const int ax = dir >> 1;
+        dx = ax == 0 ? d : 0;
+        dy = ax == 1 ? d : 0;
+        dz = ax == 2 ? d : 0;
+    }
+    x = (int)min(max((long long)x + dx, 0ll), (long long)c.vmax[0]);
+    y = (int)min(max((long long)y + dy, 0ll), (long long)c.vmax[1]);
+    z = (int)min(max((long long)z + dz, 0ll), (long long)c.vmax[2]);
 }
 
 // largest b in [0, n_scans) with start[b] <= x, given start[0] <= x < start[n_scans]

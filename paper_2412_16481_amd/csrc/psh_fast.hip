@@ -244,7 +244,7 @@ __global__ __launch_bounds__(TH) void k_pshf_step(PshArgs a, int r, const uint32
             int x = voxel_of(cx[s], cfg.mn[0], a.inv_voxel);
             int y = voxel_of(cy[s], cfg.mn[1], a.inv_voxel);
             int z = voxel_of(cz[s], cfg.mn[2], a.inv_voxel);
-            if (r > 0) probe_voxel(r, cfg, x, y, z);
+            if (r > 0) probe_voxel(a, r, cfg, x, y, z);
             h = hash_bucket(a.hash, x, y, z, cfg);
         }
         act[s] = active;

@@ -28,8 +28,9 @@ def dev(a, dtype=None):
 
 
 def run_bucketize(coords, bo, voxel, cap, m=4, hash="zorder_div", n_probes=6, max_scan_points=0, div=0, probe_step=0,
-                  schedule="auto"):
-    p = f3d.make_params(voxel, cap, m, hash, n_probes, div, probe_step, max_scan_points, schedule)
+                  schedule="auto", order="index", probe_mode="axes", probe_seed=0, probe_table=None):
+    p = f3d.make_params(voxel, cap, m, hash, n_probes, div, probe_step, max_scan_points, schedule, order, probe_mode,
+                        probe_seed, probe_table)
     bk = f3d.psh_bucketize(dev(coords), None if bo is None else dev(bo.astype(np.int32)), p)
     torch.cuda.synchronize()
     return bk
@@ -38,7 +39,9 @@ def run_bucketize(coords, bo, voxel, cap, m=4, hash="zorder_div", n_probes=6, ma
 def check_bucketize(coords, bo, voxel, cap, m=4, hash="zorder_div", n_probes=6, **kw):
     S = cap // m
     bo_arr = np.array([0, coords.shape[0]], dtype=np.int32) if bo is None else bo
-    ref = oracle.bucketize(coords, bo_arr, voxel, S, hash, n_probes, kw.get("div", 0), kw.get("probe_step", 0))
+    ref = oracle.bucketize(coords, bo_arr, voxel, S, hash, n_probes, kw.get("div", 0), kw.get("probe_step", 0),
+                           kw.get("order", "index"), kw.get("probe_mode", "axes"), kw.get("probe_seed", 0),
+                           kw.get("probe_table"))
     bk = run_bucketize(coords, bo, voxel, cap, m, hash, n_probes, **kw)
     K = len(ref["offsets"]) - 1
     assert bk.scan_bucket_start.cpu().numpy().tolist() == ref["scan_bucket_start"].tolist()
@@ -171,6 +174,100 @@ def test_inconsistent_batch_offsets_are_flagged_not_faulted():
         assert int(bk.scan_bucket_start[-1]) == -1
     bk = run_bucketize(c, np.array([0, 900, 1000]), 0.05, 64, max_scan_points=800)   # a scan above the stated bound
     assert int(bk.scan_bucket_start[-1]) == -1
+
+
+
+# ----------------------------------------------------------------------------- rebalancing variants
+
+
+def clustered_cloud(rng, n, offset=0.0):
+    centres = rng.random((12, 3)) * 6.0
+    return (centres[rng.integers(0, 12, n)] + rng.normal(0, 0.08, (n, 3)) + offset).astype(np.float32)
+
+
+@pytest.mark.parametrize("schedule", ["general", "steps"])
+@pytest.mark.parametrize("name,hash", [("tiny", "xor_mod"), ("indoor", "zorder_div"), ("lidar4", "xor_div"), ("lidar4", "zorder_mod")])
+def test_bucketize_canonical_order_matches_oracle(name, hash, schedule):
+    w = wl.make_workload(name)
+    msp = int(np.diff(w.batch_offsets).max())
+    check_bucketize(w.coords, w.batch_offsets, w.voxel_size, w.bucket_cap, w.scope_buckets, hash, order="canonical",
+                    schedule=schedule, max_scan_points=msp)
+
+
+@pytest.mark.parametrize("n", [1, 2, 63, 255, 256, 257, 2047, 2048, 2049, 6145, 30011])
+def test_bucketize_canonical_order_small_and_ragged_sizes(n):
+    rng = np.random.default_rng(300 + n)
+    c = clustered_cloud(rng, n)
+    if n > 300:
+        c[100:180] = c[100]                      # identical points: ties fall to the input index
+        c[200:260, 1:] = c[200, 1:]              # equal y and z, different x
+        c[5] = -c[5]                             # negative coordinates and a negative zero
+        c[6, 0] = -0.0
+    check_bucketize(c, None, 0.05, 128, 4, "zorder_div", order="canonical")
+
+
+def test_bucketize_canonical_order_many_scans_with_empty_ones():
+    rng = np.random.default_rng(31)
+    sizes = [0, 700, 1, 0, 5000, 2048, 333, 0]
+    bo = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    c = np.concatenate([clustered_cloud(rng, s, 3.0 * i) for i, s in enumerate(sizes)])
+    for hash in HASHES:
+        check_bucketize(c, bo, 0.05, 128, 4, hash, order="canonical")
+    sizes = [37] * 300                           # more than 256 scans: the scan index takes two digits of the sort key
+    bo = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    c = clustered_cloud(rng, int(bo[-1]))
+    check_bucketize(c, bo, 0.05, 64, 4, "zorder_div", order="canonical")
+
+
+@pytest.mark.parametrize("probe_mode", ["axes", "seeded"])
+def test_bucketize_canonical_order_is_equivariant_to_input_order_on_the_gpu(probe_mode):
+    rng = np.random.default_rng(32)
+    n0, n1 = 30001, 17777
+    c = np.concatenate([clustered_cloud(rng, n0), clustered_cloud(rng, n1, 3.0)])
+    bo = np.array([0, n0, n0 + n1], dtype=np.int32)
+    shuffle = np.concatenate([rng.permutation(n0), n0 + rng.permutation(n1)])
+    c2 = c[shuffle]
+    kw = dict(order="canonical", probe_mode=probe_mode, probe_seed=9)
+    a = run_bucketize(c, bo, 0.05, 256, **kw)
+    b = run_bucketize(c2, bo, 0.05, 256, **kw)
+    pa, pb = a.perm.cpu().numpy(), b.perm.cpu().numpy()
+    assert np.array_equal(c[pa], c2[pb])                                   # the same point in every row
+    assert torch.equal(a.offsets, b.offsets)
+    assert a.placed_per_round.cpu().numpy()[1:].sum() > 0.05 * (n0 + n1)    # overflow is common here
+    a0 = run_bucketize(c, bo, 0.05, 256, probe_mode=probe_mode, probe_seed=9)
+    b0 = run_bucketize(c2, bo, 0.05, 256, probe_mode=probe_mode, probe_seed=9)
+    assert not np.array_equal(c[a0.perm.cpu().numpy()], c2[b0.perm.cpu().numpy()])
+
+
+def test_bucketize_canonical_order_flags_bad_offsets_without_faulting():
+    rng = np.random.default_rng(33)
+    c = wl.uniform_cube(rng, 1000, 2.0)
+    for bo in ([0, 600, 400, 1000], [0, 500, 900], [5, 500, 1000], [0, 5000, 1000]):
+        bk = run_bucketize(c, np.array(bo), 0.05, 64, order="canonical")
+        assert int(bk.scan_bucket_start[-1]) == -1
+
+
+@pytest.mark.parametrize("schedule", ["general", "steps"])
+@pytest.mark.parametrize("hash", HASHES)
+def test_bucketize_probe_table_and_seeded_probes_match_oracle(hash, schedule):
+    rng = np.random.default_rng(34)
+    n0, n1 = 20000, 9001
+    c = np.concatenate([clustered_cloud(rng, n0), clustered_cloud(rng, n1, 2.0)])
+    bo = np.array([0, n0, n0 + n1], dtype=np.int32)
+    table = rng.integers(-12, 13, (6, 3))
+    kw = dict(schedule=schedule, max_scan_points=n0)
+    _, ref = check_bucketize(c, bo, 0.05, 256, 4, hash, probe_mode="table", probe_table=table, **kw)
+    assert ((ref["round_of"] > 0) & (ref["round_of"] < 7)).sum() > 100
+    for seed in (0, 1, 0xFFFFFFFF):
+        _, ref = check_bucketize(c, bo, 0.05, 256, 4, hash, probe_mode="seeded", probe_seed=seed, **kw)
+        assert ((ref["round_of"] > 0) & (ref["round_of"] < 7)).sum() > 100
+    check_bucketize(c, bo, 0.05, 256, 4, hash, n_probes=3, probe_mode="table", probe_table=table[:3], order="canonical", **kw)
+
+
+def test_bucketize_variants_on_the_indoor_workload():
+    w = wl.make_workload("indoor")
+    check_bucketize(w.coords, w.batch_offsets, w.voxel_size, w.bucket_cap, w.scope_buckets, "zorder_div",
+                    order="canonical", probe_mode="seeded", probe_seed=2024)
 
 
 # ----------------------------------------------------------------------------- attention
