@@ -111,7 +111,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="indoor", help="tiny | indoor | lidar4 | wide | lidar8")
+    ap.add_argument("--workload", default="indoor", help="tiny | indoor | lidar4 | wide | lidar8 (the five configurations) | scope8k (scope 8192)")
     ap.add_argument("--hash", default="zorder_div")
     ap.add_argument("--cpu-rows", type=int, default=-1,
                     help="query rows the oracle computes per pass (-1 = about 20 s of host work, 0 = skip)")
@@ -121,6 +121,9 @@ def main() -> int:
                     help="also time f3d_inbucket_pool (mean, tiles of 1024 rows, this reduction factor) on the attention output")
     ap.add_argument("--backward", action="store_true",
                     help="also time f3d_bucket_swin_attn_bwd (after a forward that stores the log-sum-exp) for every pass")
+    ap.add_argument("--rebalance", action="store_true",
+                    help="also time f3d_psh_bucketize with the rebalancing variants: canonical (input-order-independent) "
+                         "serving order, seeded probe directions, both")
     ap.add_argument("--glue", action="store_true",
                     help="also time f3d_ln_linear as the block's QKV projection (LayerNorm, rows gathered into bucket-major "
                          "order) and as its output projection (residual, rows scattered back)")
@@ -268,6 +271,25 @@ def main() -> int:
         res["pool"] = {"rho": rho, "tile": 1024, "op": "mean", "pooled_rows": n_out, "ms": ms, "points_per_s": n / (ms * 1e-3),
                        "roofline": {"bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                                     "frac": gbps / PEAK_HBM_GBPS, "bytes": nbytes}}
+    if args.rebalance:   # variants of Algorithm 2, outside the headline step
+        var = {}
+        for name, kw in (("index_axes", {}), ("canonical", {"order": "canonical"}), ("seeded", {"probe_mode": "seeded", "probe_seed": 1}),
+                         ("canonical_seeded", {"order": "canonical", "probe_mode": "seeded", "probe_seed": 1})):
+            pv = f3d.make_params(w.voxel_size, w.bucket_cap, m, args.hash, max_scan_points=max_scan, **kw)
+            wsv = torch.empty(f3d.workspace_bytes(n, w.n_scans, pv), dtype=torch.uint8, device=dev)
+            bkv = f3d.psh_bucketize(coords, bo, pv, wsv)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                f3d.psh_bucketize(coords, bo, pv, wsv, bkv)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / args.steps
+            pl = bkv.placed_per_round.cpu().numpy()
+            var[name] = {"ms": ms, "points_per_s": n / (ms * 1e-3), "workspace_bytes": int(wsv.numel()),
+                         "placed_share": {"direct": float(pl[0]) / n, "probes": float(pl[1:7].sum()) / n, "recycle": float(pl[7]) / n}}
+        res["rebalance_variants"] = var
     if args.backward:   # training: gradient of every pass, outside the headline step
         lse = torch.empty(n, H, dtype=torch.float32, device=dev)
         dout = torch.randn(n, C, device=dev, generator=gen, dtype=torch.float32).to(torch.bfloat16)

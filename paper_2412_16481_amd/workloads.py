@@ -171,6 +171,7 @@ def _stack_scans(scans: List[np.ndarray]) -> Tuple[np.ndarray, np.ndarray]:
 
 
 CONFIG_NAMES = ("tiny", "indoor", "lidar4", "wide", "lidar8")
+EXTRA_NAMES = ("scope8k",)
 
 
 def make_workload(name: str, seed: int = 0) -> Workload:
@@ -193,7 +194,11 @@ def make_workload(name: str, seed: int = 0) -> Workload:
     if name == "lidar8":
         c, off = _stack_scans([lidar_scan(np.random.default_rng(seed + s)) for s in range(8)])
         return Workload(name, c, off, 0.05, 1024, 8, 32, ["shift", "stride", "shift", "stride"], seed)
-    raise ValueError(f"unknown workload {name!r}; choose from {CONFIG_NAMES}")
+    if name == "scope8k":    # beyond the five configurations: the largest scope of the paper's scope-scaling study
+        rng = np.random.default_rng(seed)
+        c, off = _stack_scans([indoor_room(rng, 200_000)])
+        return Workload(name, c, off, 0.02, 8192, 8, 16, ["plain", "shift", "stride"], seed)
+    raise ValueError(f"unknown workload {name!r}; choose from {CONFIG_NAMES + EXTRA_NAMES}")
 
 
 def many_scans(n_scans: int, points_per_scan: int, seed: int = 0, side: float = 20.0) -> Tuple[np.ndarray, np.ndarray]:
