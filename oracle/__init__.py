@@ -48,6 +48,9 @@ def lib() -> ctypes.CDLL:
         _lib.orc_group_of_bucket.restype = ctypes.c_int64
         _lib.orc_group_of_bucket.argtypes = [ctypes.c_int64] + [ctypes.c_int32] * 4
         _lib.orc_attn.restype = ctypes.c_int64
+        _lib.orc_attn_fmt.restype = ctypes.c_int64
+        _lib.orc_half_to_double.restype = ctypes.c_double
+        _lib.orc_half_to_double.argtypes = [ctypes.c_uint16]
         _lib.orc_unpermute.restype = ctypes.c_int
         _lib.orc_max_threads.restype = ctypes.c_int
         _lib.orc_pool_assign.restype = ctypes.c_int64
@@ -131,10 +134,11 @@ def probe_direction(seed: int, r: int, voxel) -> int:
 
 def attn(q: np.ndarray, k: np.ndarray, v: np.ndarray, perm: Optional[np.ndarray], offsets: np.ndarray,
          scan_bucket_start: np.ndarray, scope_buckets: int, mode: str, heads: int, head_dim: int,
-         shift: int = 2, stride: int = 2, scale: Optional[float] = None, row_sel: Optional[np.ndarray] = None) -> np.ndarray:
-    """Scope-restricted multi-head self-attention in binary64. q,k,v: uint16 bf16 bit patterns
-    [n, heads*head_dim]. Returns float64 [n, heads*head_dim] in bucket-major row order (rows not
-    selected by row_sel are NaN)."""
+         shift: int = 2, stride: int = 2, scale: Optional[float] = None, row_sel: Optional[np.ndarray] = None,
+         fmt: str = "bf16") -> np.ndarray:
+    """Scope-restricted multi-head self-attention in binary64. q,k,v: uint16 bit patterns [n, heads*head_dim] of
+    bfloat16 (fmt="bf16") or binary16 (fmt="f16") numbers. Returns float64 [n, heads*head_dim] in bucket-major row
+    order (rows not selected by row_sel are NaN)."""
     q, k, v = (np.ascontiguousarray(a, dtype=np.uint16) for a in (q, k, v))
     n = q.shape[0]
     off = np.ascontiguousarray(offsets, dtype=np.int32)
@@ -143,13 +147,18 @@ def attn(q: np.ndarray, k: np.ndarray, v: np.ndarray, perm: Optional[np.ndarray]
     sel = None if row_sel is None else np.ascontiguousarray(row_sel, dtype=np.uint8)
     out = np.full((n, heads * head_dim), np.nan, dtype=np.float64)
     sc = (1.0 / np.sqrt(float(head_dim))) if scale is None else float(scale)
-    r = lib().orc_attn(_p(q), _p(k), _p(v), _p(pm), _p(off), _p(sbs), ctypes.c_int32(sbs.shape[0] - 1),
+    r = lib().orc_attn_fmt(_p(q), _p(k), _p(v), ctypes.c_int32({"bf16": 0, "f16": 1}[fmt]), _p(pm), _p(off), _p(sbs), ctypes.c_int32(sbs.shape[0] - 1),
                        ctypes.c_int32(scope_buckets), ctypes.c_int32(MODES[mode]), ctypes.c_int32(shift),
                        ctypes.c_int32(stride), ctypes.c_int32(heads), ctypes.c_int32(head_dim), ctypes.c_double(sc),
                        _p(sel), _p(out))
     if r < 0:
         raise ValueError("orc_attn: bad arguments")
     return out
+
+
+def half_to_double(bits: int) -> float:
+    """The oracle's decoder of a binary16 bit pattern."""
+    return float(lib().orc_half_to_double(ctypes.c_uint16(bits)))
 
 
 def attn_bwd(q: np.ndarray, k: np.ndarray, v: np.ndarray, dout: np.ndarray, perm: Optional[np.ndarray], offsets: np.ndarray,

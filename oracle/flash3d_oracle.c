@@ -398,19 +398,39 @@ static double bf16_to_double(uint16_t h)
     return (double)f;
 }
 
+/* IEEE-754 binary16 bit pattern to binary64, field by field (the Appendix "Bucket-Swin" keeps the features in FP16). */
+double orc_half_to_double(uint16_t h)
+{
+    const int sign = (h >> 15) & 1, ex = (h >> 10) & 31, man = h & 1023;
+    double v;
+    if (ex == 0) v = ldexp((double)man, -24);                 /* zero and subnormals */
+    else if (ex == 31) v = man ? NAN : INFINITY;
+    else v = ldexp(1.0 + (double)man / 1024.0, ex - 15);
+    return sign ? -v : v;
+}
+
+enum { ORC_FMT_BF16 = 0, ORC_FMT_F16 = 1 };
+
+static double elem_to_double(int32_t fmt, uint16_t h)
+{
+    return fmt == ORC_FMT_F16 ? orc_half_to_double(h) : bf16_to_double(h);
+}
+
 /*
- * Multi-head self-attention restricted to scopes. q,k,v are bf16 bit patterns [n, heads*head_dim].
+ * Multi-head self-attention restricted to scopes. q,k,v are 16-bit patterns [n, heads*head_dim] of bfloat16
+ * (fmt = ORC_FMT_BF16) or binary16 (fmt = ORC_FMT_F16) numbers; the arithmetic is binary64 either way.
  * Row p of the bucket-major array holds input row perm[p] (perm == NULL: inputs are already
  * bucket-major). out[p, :] (binary64, bucket-major rows) = sum_j softmax_j(q_p . k_j * scale) v_j
  * over the rows j of p's scope, head by head. row_sel (may be NULL) limits the computed query rows
  * to those with row_sel[p] != 0; other rows of out are left untouched.
  * returns the number of scopes visited, -1 on bad arguments.
  */
-int64_t orc_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, const int32_t *perm,
-                 const int32_t *offsets, const int32_t *scan_bucket_start, int32_t n_scans,
-                 int32_t m, int32_t mode, int32_t s, int32_t t, int32_t heads, int32_t head_dim,
-                 double scale, const uint8_t *row_sel, double *out)
+int64_t orc_attn_fmt(const uint16_t *q, const uint16_t *k, const uint16_t *v, int32_t fmt, const int32_t *perm,
+                     const int32_t *offsets, const int32_t *scan_bucket_start, int32_t n_scans,
+                     int32_t m, int32_t mode, int32_t s, int32_t t, int32_t heads, int32_t head_dim,
+                     double scale, const uint8_t *row_sel, double *out)
 {
+    if (fmt < 0 || fmt > 1) return -1;
     if (m <= 0 || heads <= 0 || head_dim <= 0 || mode < 0 || mode > 2) return -1;
     if (mode == ORC_SHIFT && (s <= 0 || s >= m)) return -1;
     if (mode == ORC_STRIDE && t <= 0) return -1;
@@ -450,7 +470,7 @@ int64_t orc_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, const 
                         const int64_t ib = perm ? perm[rows[bb]] : rows[bb];
                         double dot = 0.0;
                         for (int32_t e = 0; e < head_dim; ++e)
-                            dot += bf16_to_double(q[ia * C + co + e]) * bf16_to_double(k[ib * C + co + e]);
+                            dot += elem_to_double(fmt, q[ia * C + co + e]) * elem_to_double(fmt, k[ib * C + co + e]);
                         sc[bb] = dot * scale;
                         if (sc[bb] > mx) mx = sc[bb];
                     }
@@ -464,7 +484,7 @@ int64_t orc_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, const 
                         double acc = 0.0;
                         for (int64_t bb = 0; bb < ng; ++bb) {
                             const int64_t ib = perm ? perm[rows[bb]] : rows[bb];
-                            acc += sc[bb] * bf16_to_double(v[ib * C + co + e]);
+                            acc += sc[bb] * elem_to_double(fmt, v[ib * C + co + e]);
                         }
                         out[pa * C + co + e] = acc;
                     }
@@ -475,6 +495,16 @@ int64_t orc_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, const 
         }
     }
     return visited;
+}
+
+/* The bfloat16 form (the five benchmark configurations). */
+int64_t orc_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, const int32_t *perm,
+                 const int32_t *offsets, const int32_t *scan_bucket_start, int32_t n_scans,
+                 int32_t m, int32_t mode, int32_t s, int32_t t, int32_t heads, int32_t head_dim,
+                 double scale, const uint8_t *row_sel, double *out)
+{
+    return orc_attn_fmt(q, k, v, ORC_FMT_BF16, perm, offsets, scan_bucket_start, n_scans, m, mode, s, t, heads, head_dim,
+                        scale, row_sel, out);
 }
 
 /*

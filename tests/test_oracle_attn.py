@@ -267,3 +267,48 @@ def test_modes_share_one_layout():
     assert not np.array_equal(outs["plain"], outs["shift"]) and not np.array_equal(outs["plain"], outs["stride"])
     for o in outs.values():
         assert np.isfinite(o).all()
+
+
+# ----------------------------------------------------------------------------- binary16 inputs (Appendix "Bucket-Swin": FP16 features)
+
+
+def test_half_decoder_matches_numpy_on_every_bit_pattern():
+    bits = np.arange(65536, dtype=np.uint16)
+    ref = bits.view(np.float16).astype(np.float64)
+    got = np.array([oracle.half_to_double(int(b)) for b in bits])
+    assert ((got == ref) | (np.isnan(got) & np.isnan(ref))).all()
+    assert (np.signbit(got) == np.signbit(ref)).all()          # also tells -0 from +0
+
+
+@pytest.mark.parametrize("mode", ["plain", "shift", "stride"])
+def test_half_inputs_brute_force_dense_masked_attention(mode):
+    S, H, d, m = 16, 2, 16, 4
+    off, sbs = layout_full_buckets(7, S, last=9)
+    n = int(off[-1])
+    rng = np.random.default_rng(41)
+    q, k, v = ((rng.standard_normal((n, H * d)) * 1.5).astype(np.float16) for _ in range(3))
+    gid = row_groups(off, sbs, m, mode)
+    out = np.zeros((n, H * d))
+    same = gid[:, None] == gid[None, :]
+    for h in range(H):                                         # numpy's own float16 -> float64 conversion
+        sl = slice(h * d, (h + 1) * d)
+        s = q[:, sl].astype(np.float64) @ k[:, sl].astype(np.float64).T * 0.25
+        s = np.where(same, s, -np.inf)
+        p = np.exp(s - s.max(axis=1, keepdims=True))
+        out[:, sl] = (p / p.sum(axis=1, keepdims=True)) @ v[:, sl].astype(np.float64)
+    got = oracle.attn(q.view(np.uint16), k.view(np.uint16), v.view(np.uint16), None, off, sbs, m, mode, H, d, fmt="f16")
+    np.testing.assert_allclose(got, out, rtol=0, atol=1e-12)
+
+
+def test_values_exact_in_both_formats_give_the_same_result():
+    S, H, d = 16, 2, 16
+    off, sbs = layout_full_buckets(4, S, last=5)
+    n = int(off[-1])
+    rng = np.random.default_rng(42)
+    vals = [(rng.integers(-8, 9, (n, H * d)) / 4.0).astype(np.float32) for _ in range(3)]   # quarter-integers: exact in both
+    as_bf16 = [wl.f32_to_bf16_bits(x) for x in vals]
+    as_f16 = [x.astype(np.float16).view(np.uint16) for x in vals]
+    a = oracle.attn(*as_bf16, None, off, sbs, 4, "plain", H, d)
+    b = oracle.attn(*as_f16, None, off, sbs, 4, "plain", H, d, fmt="f16")
+    assert np.array_equal(a, b)
+    assert not np.array_equal(as_bf16[0], as_f16[0])           # the bit patterns do differ
