@@ -121,6 +121,9 @@ def main() -> int:
                     help="also time f3d_inbucket_pool (mean, tiles of 1024 rows, this reduction factor) on the attention output")
     ap.add_argument("--backward", action="store_true",
                     help="also time f3d_bucket_swin_attn_bwd (after a forward that stores the log-sum-exp) for every pass")
+    ap.add_argument("--dtype", default="bf16", choices=["bf16", "f16"],
+                    help="element type of q, k, v and the output: bf16 (the benchmark configurations) or f16 (the "
+                         "Appendix's FP16 features; forward path only, not with --pool/--backward/--glue)")
     ap.add_argument("--rebalance", action="store_true",
                     help="also time f3d_psh_bucketize with the rebalancing variants: canonical (input-order-independent) "
                          "serving order, seeded probe directions, both")
@@ -150,7 +153,10 @@ def main() -> int:
     coords = torch.from_numpy(w.coords).to(dev)
     bo = torch.from_numpy(w.batch_offsets).to(dev)
     gen = torch.Generator(device=dev).manual_seed(w.seed)
-    q, k, v = (torch.randn(n, C, device=dev, generator=gen, dtype=torch.float32).to(torch.bfloat16) for _ in range(3))
+    if args.dtype == "f16" and (args.pool or args.backward or args.glue):
+        sys.exit("bench.py: --dtype f16 covers the forward path only")
+    elem = torch.bfloat16 if args.dtype == "bf16" else torch.float16
+    q, k, v = (torch.randn(n, C, device=dev, generator=gen, dtype=torch.float32).to(elem) for _ in range(3))
     bucket_major = args.workload == "lidar8"      # that workload keeps its layers on bucket-major features
 
     max_scan = int(np.diff(w.batch_offsets).max())
@@ -237,7 +243,7 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": args.dtype,
         "data": "synthetic",
         "config": {"workload": w.name, "points": n, "scans": w.n_scans, "channels": C, "heads": H, "head_dim": d,
                    "bucket_cap": w.bucket_cap, "scope_buckets": m, "hash": args.hash, "passes": w.modes,

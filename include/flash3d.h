@@ -181,6 +181,19 @@ int f3d_bucket_swin_attn(const void *q, const void *k, const void *v, const int3
                          void *stream);
 
 /*
+ * The same attention on IEEE binary16 ("FP16") tensors, the element type the Appendix "Bucket-Swin" names for the
+ * point features: q, k, v and out are binary16 [n, heads*head_dim]; every other argument, the layout and the error
+ * behaviour are those of f3d_bucket_swin_attn. Arithmetic: binary16 operands, fp32 accumulation and softmax,
+ * probabilities rounded to binary16 (round to nearest even) before P*V. |q * softmax_scale * log2(e)| is
+ * clamped to 65000 (finite in binary16); scores that large saturate the softmax anyway. Forward only.
+ */
+int f3d_bucket_swin_attn_f16(const void *q, const void *k, const void *v, const int32_t *perm, const int32_t *offsets,
+                             const int32_t *scan_bucket_start, int64_t n, int32_t n_scans, int64_t max_buckets,
+                             int32_t bucket_cap, int32_t scope_buckets, int32_t mode, int32_t shift, int32_t stride,
+                             int32_t heads, int32_t head_dim, float softmax_scale, void *out, const int32_t *out_perm,
+                             float *lse, void *stream);
+
+/*
  * Backward of f3d_bucket_swin_attn (Section 4.2; the experiments report training latency): given the gradient dout of
  * the BUCKET-MAJOR output rows, the gradients of q, k and v inside every scope,
  *   P = exp(scale q k^T - lse),  dP = dout v^T,  D = rowsum(dout o out),  dS = P o (dP - D),

@@ -23,7 +23,7 @@ ORDERS = {"index": 0, "canonical": 1}
 PROBE_MODES = {"axes": 0, "table": 1, "seeded": 2}
 
 EXPORTS = ("f3d_params_default", "f3d_max_buckets", "f3d_workspace_bytes", "f3d_psh_bucketize",
-           "f3d_bucket_swin_attn", "f3d_attn_bwd_workspace_bytes", "f3d_bucket_swin_attn_bwd", "f3d_ln_linear", "f3d_pool_max_rows", "f3d_pool_workspace_bytes", "f3d_inbucket_pool",
+           "f3d_bucket_swin_attn", "f3d_bucket_swin_attn_f16", "f3d_attn_bwd_workspace_bytes", "f3d_bucket_swin_attn_bwd", "f3d_ln_linear", "f3d_pool_max_rows", "f3d_pool_workspace_bytes", "f3d_inbucket_pool",
            "f3d_unpermute", "f3d_error_string", "f3d_last_hip_error", "f3d_version")
 POOL_OPS = {"sum": 0, "mean": 1, "min": 2, "max": 3}
 
@@ -70,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.f3d_psh_bucketize.restype = ctypes.c_int
         L.f3d_bucket_swin_attn.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, i32, i32, i32, i32, i32, i32, f32, vp, vp, vp, vp]
         L.f3d_bucket_swin_attn.restype = ctypes.c_int
+        L.f3d_bucket_swin_attn_f16.argtypes = L.f3d_bucket_swin_attn.argtypes
+        L.f3d_bucket_swin_attn_f16.restype = ctypes.c_int
         L.f3d_attn_bwd_workspace_bytes.argtypes = [i64, i32, ctypes.POINTER(ctypes.c_size_t)]
         L.f3d_attn_bwd_workspace_bytes.restype = ctypes.c_int
         L.f3d_bucket_swin_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, i32, i32, i32, i32, i32, i32, f32,
@@ -195,16 +197,20 @@ def psh_bucketize(coords, batch_offsets, params: f3d_params, workspace=None, out
 def bucket_swin_attn(q, k, v, buckets: Buckets, heads: int, head_dim: int, mode: str = "plain", shift: int = 2,
                      stride: int = 2, use_perm: bool = True, softmax_scale: float = 0.0, out=None, original_order: bool = False,
                      lse=None):
-    """f3d_bucket_swin_attn. q,k,v: bfloat16 [n, heads*head_dim]; rows in input order when use_perm, else
-    already bucket-major. Returns bfloat16 [n, heads*head_dim] in bucket-major row order, or, with
-    original_order, in the input order of the points (the unpermute folded into the kernel's store). lse: optional
-    float32 [n, heads] tensor that receives the rows' log-sum-exp (bucket-major), for the backward pass."""
+    """f3d_bucket_swin_attn (bfloat16 tensors) or f3d_bucket_swin_attn_f16 (float16 tensors), by the dtype of q.
+    q,k,v: [n, heads*head_dim]; rows in input order when use_perm, else already bucket-major. Returns the same dtype
+    [n, heads*head_dim] in bucket-major row order, or, with original_order, in the input order of the points (the
+    unpermute folded into the kernel's store). lse: optional float32 [n, heads] tensor that receives the rows'
+    log-sum-exp (bucket-major), for the backward pass."""
     import torch
+    assert q.dtype in (torch.bfloat16, torch.float16)
     for t in (q, k, v):
-        assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.shape == (buckets.n, heads * head_dim)
+        assert t.is_cuda and t.dtype == q.dtype and t.is_contiguous() and t.shape == (buckets.n, heads * head_dim)
     if out is None:
         out = torch.empty_like(q)
-    rc = lib().f3d_bucket_swin_attn(_ptr(q), _ptr(k), _ptr(v), _ptr(buckets.perm) if use_perm else None,
+    assert out.dtype == q.dtype
+    entry = lib().f3d_bucket_swin_attn if q.dtype == torch.bfloat16 else lib().f3d_bucket_swin_attn_f16
+    rc = entry(_ptr(q), _ptr(k), _ptr(v), _ptr(buckets.perm) if use_perm else None,
                                     _ptr(buckets.offsets), _ptr(buckets.scan_bucket_start), buckets.n, buckets.n_scans,
                                     buckets.max_buckets, buckets.bucket_cap, buckets.scope_buckets, MODES[mode] if isinstance(mode, str) else mode,
                                     shift, stride, heads, head_dim, softmax_scale, _ptr(out),

@@ -27,6 +27,7 @@ struct AttnArgs {
     int n_slots;  // scope slots over all scans (upper bound, surplus workgroups exit)
     int qblocks;  // query blocks per scope = ceil(bucket_cap / attn_block_rows(...))
     int extra;    // spare slots per scan: 2 (plain, shift) or stride + 1
+    int f16;      // 0: q, k, v, out are bfloat16; 1: binary16 (forward only)
 };
 
 // Backward pass: the forward arguments (f.out = the forward output O, f.lse = its log-sum-exp, f.out_perm = where a

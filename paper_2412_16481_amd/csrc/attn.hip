@@ -12,6 +12,10 @@
 // For head_dim 16 the second MFMA has 16 spare output rows; row 16 multiplies P by ones, which yields the
 // softmax denominator on the matrix core instead of the vector ALU.
 // The K and V^T fragments of a key tile are read from LDS once and used for all QT query tiles of the wave.
+//
+// The element type is bfloat16 (the benchmark configurations) or binary16 (the Appendix keeps the features in FP16):
+// same kernel, other MFMA and conversion instructions. binary16 probabilities overflow at 2^16, so the optimistic
+// sweep described below is accepted only for denominators in a much narrower window.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -24,9 +28,63 @@ namespace f3d {
 
 namespace {
 
-template <int D, int QT>
+// what depends on the 16-bit element type
+template <bool F16>
+struct Elem;
+template <>
+struct Elem<false> {
+    static constexpr uint16_t ONE = 0x3F80;
+    static constexpr float DEN_LO = 9.094947e-13f, DEN_HI = 1.2089258e24f;   // 2^-40, 2^80
+    static __device__ __forceinline__ uint32_t pack(float lo, float hi) { return pack_bf16(lo, hi); }
+    static __device__ __forceinline__ float lo(uint32_t w) { return __uint_as_float(w << 16); }
+    static __device__ __forceinline__ float hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+    static __device__ __forceinline__ f32x16 mfma(const U4& x, const U4& y, f32x16 c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.b, y.b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ float sum2(uint32_t pair, float c)   // c + both halves of the pair
+    {
+        const uint32_t ones = 0x3F803F80u;
+        return __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<const bf16x2*>(&pair), *reinterpret_cast<const bf16x2*>(&ones), c, false);
+    }
+};
+template <>
+struct Elem<true> {
+    static constexpr uint16_t ONE = 0x3C00;
+    // a probability above 65504 rounds to infinity (and so does the denominator); below 2^-3 the terms that carry the
+    // sum may be subnormal with fewer than eight significant bits
+    static constexpr float DEN_LO = 0.125f, DEN_HI = 1.0737418e9f;           // 2^-3, 2^30
+    static __device__ __forceinline__ uint32_t pack(float lo, float hi)
+    {
+        f32x2 x = {lo, hi};
+        f16x2 y = __builtin_convertvector(x, f16x2);   // round to nearest even, overflow to infinity
+        return *reinterpret_cast<uint32_t*>(&y);
+    }
+    static __device__ __forceinline__ float lo(uint32_t w)
+    {
+        const f16x2 h = *reinterpret_cast<const f16x2*>(&w);
+        return (float)h[0];
+    }
+    static __device__ __forceinline__ float hi(uint32_t w)
+    {
+        const f16x2 h = *reinterpret_cast<const f16x2*>(&w);
+        return (float)h[1];
+    }
+    static __device__ __forceinline__ f32x16 mfma(const U4& x, const U4& y, f32x16 c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(x.f, y.f, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ float sum2(uint32_t pair, float c)
+    {
+        const uint32_t ones = 0x3C003C00u;
+        return __builtin_amdgcn_fdot2(*reinterpret_cast<const f16x2*>(&pair), *reinterpret_cast<const f16x2*>(&ones), c, false);
+    }
+};
+
+template <int D, int QT, bool F16>
 __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
 {
+    using E = Elem<F16>;
     constexpr int NC = D / 8;              // 16-byte chunks of one head in a row
     constexpr int KS = D / 16;             // MFMA k-steps for Q K^T
     constexpr int LPT = KT * NC / 256;     // 16-byte loads per thread per stage and tensor
@@ -158,16 +216,16 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
     // head_dim 16: rows 16 and 17 of V^T are constants (ones -> softmax denominator, zeros -> unused rows)
     if (D == 16) {
         for (int i = tid; i < 2 * VSTR; i += 256) {
-            const uint16_t val = i < VSTR ? 0x3F80 : 0;
+            const uint16_t val = i < VSTR ? E::ONE : 0;
             sV[0][D * VSTR + i] = val;
             sV[1][D * VSTR + i] = val;
         }
     }
 
-    // The query fragment is pre-multiplied by softmax_scale*log2(e) and split into a bf16 head and a bf16
+    // The query fragment is pre-multiplied by softmax_scale*log2(e) and split into a 16-bit head and a 16-bit
     // remainder (q*c = hi + lo up to 2^-17 relative), so the MFMA delivers the scaled score directly. The
     // vector ALU is the busy unit of this kernel, the matrix core is not: one more MFMA per tile is cheaper
-    // than 16 multiplies.
+    // than 16 multiplies. (binary16: the product is kept inside the finite range of the format.)
     U4 qhi[QT][KS], qlo[QT][KS];
     {
         const float cl2 = a.c_log2;
@@ -178,11 +236,15 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const uint32_t w2 = (&qf[t][ks].u.x)[e];
-                    const float x0 = __uint_as_float(w2 << 16) * cl2, x1 = __uint_as_float(w2 & 0xFFFF0000u) * cl2;
-                    const uint32_t h = pack_bf16(x0, x1);
-                    const float r0 = x0 - __uint_as_float(h << 16), r1 = x1 - __uint_as_float(h & 0xFFFF0000u);
+                    float x0 = E::lo(w2) * cl2, x1 = E::hi(w2) * cl2;
+                    if (F16) {
+                        x0 = fminf(fmaxf(x0, -65000.f), 65000.f);
+                        x1 = fminf(fmaxf(x1, -65000.f), 65000.f);
+                    }
+                    const uint32_t h = E::pack(x0, x1);
+                    const float r0 = x0 - E::lo(h), r1 = x1 - E::hi(h);
                     (&qhi[t][ks].u.x)[e] = h;
-                    (&qlo[t][ks].u.x)[e] = pack_bf16(r0, r1);
+                    (&qlo[t][ks].u.x)[e] = E::pack(r0, r1);
                 }
             }
         }
@@ -192,7 +254,6 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
     // this lane's row of V^T: a head dim, or the ones row, or the zeros row
     const int vrow = (D == 16) ? min(l32, 17) : l32;
     const int voff = vrow * VSTR + 8 * hf;
-    const uint32_t ones2 = 0x3F803F80u;
 
     f32x16 o[QT];
     float l_run[QT], den[QT], mfin[QT];   // mfin: the reference the final sweep's exponentials were taken against
@@ -248,8 +309,8 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
                     s[t] = f32x16{0};
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) {
-                        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks].b, qhi[t][ks].b, s[t], 0, 0, 0);
-                        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks].b, qlo[t][ks].b, s[t], 0, 0, 0);
+                        s[t] = E::mfma(kf[ks], qhi[t][ks], s[t]);
+                        s[t] = E::mfma(kf[ks], qlo[t][ks], s[t]);
                     }
                 }
 #pragma unroll
@@ -287,23 +348,21 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
                     }
 #pragma unroll
                     for (int r = 0; r < 16; ++r) s[t][r] = __builtin_amdgcn_exp2f(s[t][r]);
-                    union { uint32_t u[4]; bf16x8 b; } pb0, pb1;
+                    U4 pb0, pb1;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        pb0.u[e] = pack_bf16(s[t][2 * e], s[t][2 * e + 1]);
-                        pb1.u[e] = pack_bf16(s[t][8 + 2 * e], s[t][8 + 2 * e + 1]);
+                        (&pb0.u.x)[e] = E::pack(s[t][2 * e], s[t][2 * e + 1]);
+                        (&pb1.u.x)[e] = E::pack(s[t][8 + 2 * e], s[t][8 + 2 * e + 1]);
                     }
                     if (D == 32) {   // denominator from the rounded probabilities, two per instruction
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            l_run[t] = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<bf16x2*>(&pb0.u[e]),
-                                                                       *reinterpret_cast<const bf16x2*>(&ones2), l_run[t], false);
-                            l_run[t] = __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<bf16x2*>(&pb1.u[e]),
-                                                                       *reinterpret_cast<const bf16x2*>(&ones2), l_run[t], false);
+                            l_run[t] = E::sum2((&pb0.u.x)[e], l_run[t]);
+                            l_run[t] = E::sum2((&pb1.u.x)[e], l_run[t]);
                         }
                     }
-                    o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf0.b, pb0.b, o[t], 0, 0, 0);
-                    o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf1.b, pb1.b, o[t], 0, 0, 0);
+                    o[t] = E::mfma(vf0, pb0, o[t]);
+                    o[t] = E::mfma(vf1, pb1, o[t]);
                 }
             }
             if (st + 1 < nst) store_stage(buf ^ 1);
@@ -322,14 +381,15 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
 
     sweep(std::false_type{});
     {
-        // 2^-40 < den < 2^80: no exponential overflowed, and the largest one is far above the flush-to-zero range
+        // bfloat16: 2^-40 < den < 2^80: no exponential overflowed, and the largest one is far above the flush-to-zero
+        // range. binary16: 2^-3 < den < 2^30, see Elem<true>.
         bool bad = false;
 #pragma unroll
-        for (int t = 0; t < QT; ++t) bad = bad || ((orow[t] >= 0) && !(den[t] > 9.094947e-13f && den[t] < 1.2089258e24f));
+        for (int t = 0; t < QT; ++t) bad = bad || ((orow[t] >= 0) && !(den[t] > E::DEN_LO && den[t] < E::DEN_HI));
         if (__syncthreads_or(bad)) sweep(std::true_type{});
     }
 
-    // ---- epilogue: divide by the softmax denominator, round to bf16, store
+    // ---- epilogue: divide by the softmax denominator, round to the element type, store
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
         if (orow[t] >= 0) {
@@ -343,8 +403,8 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
 #pragma unroll
             for (int blk = 0; blk < NB; ++blk) {
                 uint2 pk;
-                pk.x = pack_bf16(o[t][4 * blk] * inv, o[t][4 * blk + 1] * inv);
-                pk.y = pack_bf16(o[t][4 * blk + 2] * inv, o[t][4 * blk + 3] * inv);
+                pk.x = E::pack(o[t][4 * blk] * inv, o[t][4 * blk + 1] * inv);
+                pk.y = E::pack(o[t][4 * blk + 2] * inv, o[t][4 * blk + 3] * inv);
                 *reinterpret_cast<uint2*>(dst + 8 * blk + 4 * hf) = pk;
             }
         }
@@ -373,12 +433,19 @@ hipError_t attn_launch(const AttnArgs& a, int head_dim, int block_rows, hipStrea
     long long total = (long long)a.n_slots * a.H * a.qblocks;
     total = (total + 7) / 8 * 8;
     if (total == 0) return hipSuccess;
-    if (head_dim == 16 && block_rows == 256)
-        k_attn<16, 2><<<(unsigned)total, 256, 0, stream>>>(a);
+    if (a.f16) {
+        if (head_dim == 16 && block_rows == 256)
+            k_attn<16, 2, true><<<(unsigned)total, 256, 0, stream>>>(a);
+        else if (head_dim == 16)
+            k_attn<16, 1, true><<<(unsigned)total, 256, 0, stream>>>(a);
+        else
+            k_attn<32, 1, true><<<(unsigned)total, 256, 0, stream>>>(a);
+    } else if (head_dim == 16 && block_rows == 256)
+        k_attn<16, 2, false><<<(unsigned)total, 256, 0, stream>>>(a);
     else if (head_dim == 16)
-        k_attn<16, 1><<<(unsigned)total, 256, 0, stream>>>(a);
+        k_attn<16, 1, false><<<(unsigned)total, 256, 0, stream>>>(a);
     else
-        k_attn<32, 1><<<(unsigned)total, 256, 0, stream>>>(a);
+        k_attn<32, 1, false><<<(unsigned)total, 256, 0, stream>>>(a);
     return hipGetLastError();
 }
 

@@ -290,10 +290,10 @@ static int fill_attn_args(f3d::AttnArgs& a, const void* q, const void* k, const 
     return F3D_OK;
 }
 
-int f3d_bucket_swin_attn(const void* q, const void* k, const void* v, const int32_t* perm, const int32_t* offsets,
-                         const int32_t* scan_bucket_start, int64_t n, int32_t n_scans, int64_t max_buckets,
-                         int32_t bucket_cap, int32_t scope_buckets, int32_t mode, int32_t shift, int32_t stride, int32_t heads,
-                         int32_t head_dim, float softmax_scale, void* out, const int32_t* out_perm, float* lse, void* stream)
+static int attn_forward(int f16, const void* q, const void* k, const void* v, const int32_t* perm, const int32_t* offsets,
+                        const int32_t* scan_bucket_start, int64_t n, int32_t n_scans, int64_t max_buckets, int32_t bucket_cap,
+                        int32_t scope_buckets, int32_t mode, int32_t shift, int32_t stride, int32_t heads, int32_t head_dim,
+                        float softmax_scale, void* out, const int32_t* out_perm, float* lse, void* stream)
 {
     f3d::AttnArgs a;
     float scale;
@@ -308,6 +308,7 @@ int f3d_bucket_swin_attn(const void* q, const void* k, const void* v, const int3
     a.out = (uint16_t*)out;
     a.out_perm = out_perm;
     a.lse = lse;
+    a.f16 = f16;
     const int bm = f3d::attn_block_rows(head_dim, slots, heads, bucket_cap);
     a.qblocks = (bucket_cap + bm - 1) / bm;
     if (slots * heads * a.qblocks > 2000000000ll) return F3D_ERR_UNSUPPORTED;
@@ -315,6 +316,24 @@ int f3d_bucket_swin_attn(const void* q, const void* k, const void* v, const int3
     (void)hipGetLastError();
     const hipError_t e = f3d::attn_launch(a, head_dim, bm, (hipStream_t)stream);
     return e == hipSuccess ? F3D_OK : hip_fail(e);
+}
+
+int f3d_bucket_swin_attn(const void* q, const void* k, const void* v, const int32_t* perm, const int32_t* offsets,
+                         const int32_t* scan_bucket_start, int64_t n, int32_t n_scans, int64_t max_buckets,
+                         int32_t bucket_cap, int32_t scope_buckets, int32_t mode, int32_t shift, int32_t stride, int32_t heads,
+                         int32_t head_dim, float softmax_scale, void* out, const int32_t* out_perm, float* lse, void* stream)
+{
+    return attn_forward(0, q, k, v, perm, offsets, scan_bucket_start, n, n_scans, max_buckets, bucket_cap, scope_buckets, mode,
+                        shift, stride, heads, head_dim, softmax_scale, out, out_perm, lse, stream);
+}
+
+int f3d_bucket_swin_attn_f16(const void* q, const void* k, const void* v, const int32_t* perm, const int32_t* offsets,
+                             const int32_t* scan_bucket_start, int64_t n, int32_t n_scans, int64_t max_buckets,
+                             int32_t bucket_cap, int32_t scope_buckets, int32_t mode, int32_t shift, int32_t stride, int32_t heads,
+                             int32_t head_dim, float softmax_scale, void* out, const int32_t* out_perm, float* lse, void* stream)
+{
+    return attn_forward(1, q, k, v, perm, offsets, scan_bucket_start, n, n_scans, max_buckets, bucket_cap, scope_buckets, mode,
+                        shift, stride, heads, head_dim, softmax_scale, out, out_perm, lse, stream);
 }
 
 int f3d_attn_bwd_workspace_bytes(int64_t n, int32_t heads, size_t* out_bytes)

@@ -411,6 +411,114 @@ def test_attention_log_sum_exp_output():
             assert np.abs(lse.cpu().numpy() - want).max() <= 4e-3
 
 
+# ----------------------------------------------------------------------------- attention on binary16 tensors
+
+ATOL_F16 = 3e-3   # output rounding 2^-12*|o| (|o| < 4: 1e-3), probabilities rounded to binary16 (2^-12 each), fp32 sums
+
+
+def attn_case_f16(q, k, v, bk, ref_layout, heads, d, mode, use_perm, rows=None, shift=2, stride=2, scale=0.0, atol=ATOL_F16,
+                  original_order=False):
+    """q, k, v: numpy float16 arrays. The binary16 entry point against the oracle fed with the same bit patterns."""
+    n = q.shape[0]
+    out = f3d.bucket_swin_attn(dev(q), dev(k), dev(v), bk, heads, d, mode, shift, stride, use_perm, scale,
+                               original_order=original_order)
+    torch.cuda.synchronize()
+    assert out.dtype == torch.float16
+    got = out.float().cpu().numpy().astype(np.float64)
+    if original_order:
+        got = got[ref_layout["perm"]]
+    sel = None
+    if rows is not None:
+        sel = np.zeros(n, dtype=np.uint8)
+        sel[rows] = 1
+    ref = oracle.attn(q.view(np.uint16), k.view(np.uint16), v.view(np.uint16), ref_layout["perm"] if use_perm else None,
+                      ref_layout["offsets"], ref_layout["scan_bucket_start"], bk.scope_buckets, mode, heads, d, shift, stride,
+                      None if scale == 0.0 else scale, sel, fmt="f16")
+    mask = slice(None) if rows is None else rows
+    err = np.abs(got[mask] - ref[mask])
+    assert np.isfinite(got).all()
+    assert err.max() <= atol, f"max-abs {err.max():.4g} (mean {err.mean():.3g})"
+    return err.max()
+
+
+@pytest.mark.parametrize("d,heads", [(16, 2), (32, 2), (16, 5)])
+def test_attention_f16_ragged_buckets_all_modes(d, heads):
+    sizes = [[64, 64, 37, 64, 1, 64, 64, 64, 50], [17], [64, 64, 64, 64, 64, 3]]
+    bk, ref, n = hand_layout(sizes, 256, 4)
+    rng = np.random.default_rng(61)
+    q, k, v = (rng.standard_normal((n, heads * d)).astype(np.float16) for _ in range(3))
+    for mode, kw in (("plain", {}), ("shift", {"shift": 1}), ("shift", {"shift": 3}), ("stride", {"stride": 2}),
+                     ("stride", {"stride": 3})):
+        attn_case_f16(q, k, v, bk, ref, heads, d, mode, True, **kw)
+        attn_case_f16(q, k, v, bk, ref, heads, d, mode, False, **kw)
+    attn_case_f16(q, k, v, bk, ref, heads, d, "shift", True, original_order=True)   # the store in input order
+
+
+@pytest.mark.parametrize("name", ["tiny", "indoor", "lidar8"])
+def test_attention_f16_on_workloads(name):
+    w = wl.make_workload(name)
+    bk, ref = check_bucketize(w.coords, w.batch_offsets, w.voxel_size, w.bucket_cap)
+    rng = np.random.default_rng(62)
+    q, k, v = (rng.standard_normal((w.n, w.channels)).astype(np.float16) for _ in range(3))
+    rows = None if name == "tiny" else sample_rows(rng, ref, w.n, 600 if w.channels <= 128 else 300)
+    for mode in dict.fromkeys(w.modes):
+        attn_case_f16(q, k, v, bk, ref, w.heads, w.head_dim, mode, True, rows)
+
+
+def test_attention_f16_scores_outside_the_optimistic_window():
+    """binary16 probabilities overflow at 2^16 and vanish below 2^-24: large positive scores, uniformly very negative
+    scores and a mix of both must all end in the running-maximum sweep and stay within tolerance."""
+    bk, ref, n = hand_layout([[64] * 8 + [20]], 256, 4)
+    rng = np.random.default_rng(63)
+    base = rng.standard_normal((n, 32))
+    # peaked: scores of order +-60
+    attn_case_f16((base * 8).astype(np.float16), (rng.standard_normal((n, 32)) * 8).astype(np.float16),
+                  rng.standard_normal((n, 32)).astype(np.float16), bk, ref, 2, 16, "plain", True)
+    # every score about -40 (natural-log units): all probabilities vanish against the fixed reference
+    qn = np.full((n, 32), 2.0) + 0.05 * base
+    kn = np.full((n, 32), -5.0) + 0.05 * rng.standard_normal((n, 32))
+    attn_case_f16(qn.astype(np.float16), kn.astype(np.float16), rng.standard_normal((n, 32)).astype(np.float16), bk, ref, 2, 16,
+                  "shift", True)
+    # every score about +40: every probability overflows against the fixed reference
+    attn_case_f16(qn.astype(np.float16), (-kn).astype(np.float16), rng.standard_normal((n, 32)).astype(np.float16), bk, ref, 2, 16,
+                  "stride", True)
+    # head_dim 32, where the denominator is summed on the vector unit
+    q32 = (rng.standard_normal((n, 64)) * 6).astype(np.float16)
+    k32 = (rng.standard_normal((n, 64)) * 6).astype(np.float16)
+    attn_case_f16(q32, k32, rng.standard_normal((n, 64)).astype(np.float16), bk, ref, 2, 32, "plain", True)
+
+
+def test_attention_f16_log_sum_exp_and_largest_finite_inputs():
+    bk, ref, n = hand_layout([[64, 64, 37, 64, 1, 64, 64, 64, 50], [17]], 256, 4)
+    rng = np.random.default_rng(64)
+    q, k, v = (rng.standard_normal((n, 32)).astype(np.float16) for _ in range(3))
+    lse = torch.empty(n, 2, dtype=torch.float32, device=DEV)
+    f3d.bucket_swin_attn(dev(q), dev(k), dev(v), bk, 2, 16, "shift", lse=lse)
+    torch.cuda.synchronize()
+    # the oracle's log-sum-exp comes with its bf16 gradient routine; for binary16 it is written out here in numpy
+    from test_oracle_attn import row_groups
+    qf, kf = q.astype(np.float64), k.astype(np.float64)
+    gid = row_groups(ref["offsets"], ref["scan_bucket_start"], 4, "shift")
+    want = np.zeros((n, 2))
+    for h in range(2):
+        sl = slice(16 * h, 16 * h + 16)
+        qs, ks = qf[ref["perm"]][:, sl], kf[ref["perm"]][:, sl]                  # bucket-major rows
+        s = qs @ ks.T * 0.25
+        s = np.where(gid[:, None] == gid[None, :], s, -np.inf)
+        mx = s.max(axis=1)
+        want[:, h] = mx + np.log(np.exp(s - mx[:, None]).sum(axis=1))
+    assert np.abs(lse.cpu().numpy() - want).max() <= 2e-3
+    # the largest finite values as values (the output is a convex combination: it must stay finite and close)
+    vbig = np.where(rng.random((n, 32)) < 0.5, 65504.0, -65504.0).astype(np.float16)
+    out = f3d.bucket_swin_attn(dev(q), dev(k), dev(vbig), bk, 2, 16, "plain")
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().astype(np.float64)
+    want_o = oracle.attn(q.view(np.uint16), k.view(np.uint16), vbig.view(np.uint16), ref["perm"], ref["offsets"],
+                         ref["scan_bucket_start"], 4, "plain", 2, 16, fmt="f16")
+    assert np.isfinite(got).all()
+    assert np.abs(got - want_o).max() <= 2.0 ** -9 * 65504.0
+
+
 # ----------------------------------------------------------------------------- attention backward
 
 
