@@ -5,11 +5,12 @@
 //
 //   y[p] = LN(x[row_in[p]]) W^T + bias;   out[row_out[p]] = y[p] + residual[row_out[p]]
 //
-// One workgroup = 128 rows. The rows are normalised in place in LDS (two threads per row), rounded to bf16 and kept in
-// LDS for the whole workgroup; the weight matrix (resident in L2) is read straight from memory, once per workgroup,
-// as the A operand of v_mfma_f32_32x32x16_bf16 computing the TRANSPOSED product Y^T = W X^T, so that a lane
-// owns one row of Y and, with the rows of W taken in a suitable order, 16 consecutive columns of it: 16-byte stores,
-// no shuffles.
+// One workgroup = 4 waves = 128 rows; a wave owns 32 rows and keeps them in registers for the whole kernel, in the
+// layout of the B operand of v_mfma_f32_32x32x16_bf16 (a lane holds half of one row), normalised there and rounded
+// to bf16. The weight matrix (resident in L2) streams through LDS in double-buffered tiles of 16 KB, loaded with whole
+// rows per wave (coalesced) once per workgroup, and is the A operand of the TRANSPOSED product Y^T = W X^T: a lane
+// then owns one row of Y and, with the rows of W stored in a suitable order, 16 consecutive columns of it: 16-byte
+// stores, no shuffles.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -38,159 +39,203 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi)
 __device__ __forceinline__ float lo16(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float hi16(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
-constexpr int LBM = 128;   // rows per workgroup
-constexpr int LTH = 256;   // threads per workgroup
-constexpr int TPR = LTH / LBM;   // threads per row in the LayerNorm
+constexpr int LNW = 4;          // waves per workgroup; a wave owns 32 rows
+constexpr int LTH = LNW * 64;
+constexpr int LBM = LNW * 32;   // rows per workgroup
 
-// dynamic LDS: X tile [LBM][CI + 8] bf16
+// W tiles in LDS: 32 * TCB output columns x CI inputs, TCB chosen so that a tile is 1024 16-byte pieces (16 KB) and a
+// wave runs 16 MFMAs per tile and barrier whatever the width.
 template <int CI>
-__global__ __launch_bounds__(LTH) void k_ln_linear(LinearArgs a)
+struct Tile {
+    static constexpr int TCB = 256 / CI;            // 32-column blocks per tile
+    static constexpr int TROWS = 32 * TCB;          // rows of W (output columns) per tile
+    static constexpr int PITCH = CI + 8;            // elements; the 16-byte pad staggers the banks of consecutive rows
+    static constexpr size_t LDS_BYTES = (size_t)2 * TROWS * PITCH * 2;
+};
+
+template <int CI>
+__global__ __launch_bounds__(LTH, 3) void k_ln_linear(LinearArgs a)
 {
-    constexpr int PITCH = CI + 8;      // elements; the 16-byte pad staggers the banks of consecutive rows
-    constexpr int KS = CI / 16;        // MFMA k-steps
-    constexpr int CPT = CI / 8 / TPR;  // 16-byte pieces per thread in the LayerNorm (TPR threads per row)
-    extern __shared__ __attribute__((aligned(16))) uint16_t sx[];
+    constexpr int KS = CI / 16;                     // MFMA k-steps
+    constexpr int TCB = Tile<CI>::TCB, TROWS = Tile<CI>::TROWS, PITCH = Tile<CI>::PITCH;
+    constexpr int CPR = CI / 8;                     // 16-byte pieces per row of W
+    constexpr int PPT = TROWS * CPR / LTH;          // pieces per thread and tile (4)
+    static_assert(TROWS * CPR % LTH == 0, "a W tile is a whole number of pieces per thread");
+    extern __shared__ __attribute__((aligned(16))) uint16_t sw[];   // [2][TROWS][PITCH], then the bias as binary32 [c_out]
+    float* sbias = reinterpret_cast<float*>(sw + 2 * TROWS * PITCH);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hf = lane >> 5;
-    const long long row0 = (long long)blockIdx.x * LBM;
+    const long long p = (long long)blockIdx.x * LBM + wave * 32 + l32;   // this lane's row of Y
+    const bool ok = p < a.n;
+    const int n_cb = a.c_out >> 5;                  // 32-column blocks of the output
+    const int n_tiles = (n_cb + TCB - 1) / TCB;
 
-    // ---- load the rows into LDS, then normalise them in place: thread (r, half) handles 1/TPR of row r. The three
-    //      passes (sum; squared deviations; scale and shift) walk over the thread's own 16-byte pieces in LDS, so no
-    //      pass keeps a row in registers.
+    // ---- staging of W tiles: global -> registers (coalesced: whole rows of W) -> LDS. Row j of a 32-row block is
+    //      stored at slot 8*((j>>2)&3) + 4*(j>>4) + (j&3), so that MFMA row i holds output column
+    //      16*((i>>2)&1) + 4*(i>>3) + (i&3) of the block: with this order the 16 accumulator registers of a lane are 16
+    //      CONSECUTIVE columns of its row (two 16-byte stores; the two half-waves of a row write 64 contiguous bytes).
+    uint4 wreg[PPT];
+    const auto load_tile = [&](int t) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < PPT; ++i) {
+            const int q = tid + i * LTH;
+            const int j = q / CPR, c = q % CPR;
+            const int col = t * TROWS + j;
+            wreg[i] = col < a.c_out ? *reinterpret_cast<const uint4*>(a.w + (size_t)col * CI + 8 * c) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    const auto store_tile = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < PPT; ++i) {
+            const int q = tid + i * LTH;
+            const int j = q / CPR, c = q % CPR;
+            const int jr = j & 31;
+            const int slot = (j & ~31) + 8 * ((jr >> 2) & 3) + 4 * (jr >> 4) + (jr & 3);
+            *reinterpret_cast<uint4*>(&sw[(size_t)buf * TROWS * PITCH + slot * PITCH + 8 * c]) = wreg[i];
+        }
+    };
+    load_tile(0);
+    if (a.bias)   // read by every wave for every tile: kept in LDS, off the vector memory path
+        for (int i = tid; i < a.c_out; i += LTH) sbias[i] = a.bias[i];
+
+    // ---- this lane's part of its row: elements 16*ks + 8*hf .. +7 for every k-step, i.e. the B operand of the MFMAs.
+    //      The row stays in registers for the whole kernel.
+    F8 xf[KS];
     {
-        const int r = tid / TPR, half = tid % TPR;
-        const long long p = row0 + r;
-        const bool ok = p < a.n;
         const size_t src = ok ? (size_t)(a.row_in ? a.row_in[p] : p) : 0;
-        const uint4* xr = reinterpret_cast<const uint4*>(a.x + src * CI) + half * CPT;
-        uint4* mine = reinterpret_cast<uint4*>(&sx[r * PITCH + half * (CI / TPR)]);
+        const uint16_t* xr = a.x + src * CI + 8 * hf;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) xf[ks].u = ok ? *reinterpret_cast<const uint4*>(xr + 16 * ks) : make_uint4(0, 0, 0, 0);
+    }
+    if (a.gamma) {   // LayerNorm: the two half-waves hold the two halves of a row
+        // Between the three passes the packed words are made opaque, so that each pass unpacks them again instead of
+        // keeping the whole row alive as binary32 values.
+        const auto opaque = [&]() __attribute__((always_inline)) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(xf[ks].u.x), "+v"(xf[ks].u.y), "+v"(xf[ks].u.z), "+v"(xf[ks].u.w));
+        };
         float sum = 0.f;
 #pragma unroll
-        for (int c = 0; c < CPT; ++c) {
-            const uint4 v = ok ? xr[c] : make_uint4(0, 0, 0, 0);
-            mine[c] = v;
-            sum += (lo16(v.x) + hi16(v.x)) + (lo16(v.y) + hi16(v.y)) + (lo16(v.z) + hi16(v.z)) + (lo16(v.w) + hi16(v.w));
+        for (int ks = 0; ks < KS; ++ks) {
+            const uint32_t w4[4] = {xf[ks].u.x, xf[ks].u.y, xf[ks].u.z, xf[ks].u.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sum += lo16(w4[e]) + hi16(w4[e]);
         }
-        if (a.gamma) {
-            sum += __shfl_xor(sum, 1, 64);
-            if (TPR == 4) sum += __shfl_xor(sum, 2, 64);
-            const float mu = sum * (1.0f / CI);
-            float sq = 0.f;
-#pragma unroll 4
-            for (int c = 0; c < CPT; ++c) {
-                const uint4 v = mine[c];
-                const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
+        sum += __shfl_xor(sum, 32, 64);
+        const float mu = sum * (1.0f / CI);
+        opaque();
+        float sq = 0.f;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float d0 = lo16(w4[e]) - mu, d1 = hi16(w4[e]) - mu;
-                    sq += d0 * d0 + d1 * d1;
-                }
-            }
-            sq += __shfl_xor(sq, 1, 64);
-            if (TPR == 4) sq += __shfl_xor(sq, 2, 64);
-            const float rstd = rsqrtf(sq * (1.0f / CI) + a.eps);
-            const float4* g4 = reinterpret_cast<const float4*>(a.gamma) + half * CPT * 2;
-            const float4* b4 = a.beta ? reinterpret_cast<const float4*>(a.beta) + half * CPT * 2 : nullptr;
-#pragma unroll 2
-            for (int c = 0; c < CPT; ++c) {
-                const uint4 v = mine[c];
-                const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
-                const float4 ga = g4[2 * c], gb = g4[2 * c + 1];
-                const float4 ba = b4 ? b4[2 * c] : make_float4(0, 0, 0, 0), bb = b4 ? b4[2 * c + 1] : make_float4(0, 0, 0, 0);
-                const float gg[8] = {ga.x, ga.y, ga.z, ga.w, gb.x, gb.y, gb.z, gb.w};
-                const float bt[8] = {ba.x, ba.y, ba.z, ba.w, bb.x, bb.y, bb.z, bb.w};
-                uint32_t o[4];
+        for (int ks = 0; ks < KS; ++ks) {
+            const uint32_t w4[4] = {xf[ks].u.x, xf[ks].u.y, xf[ks].u.z, xf[ks].u.w};
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    o[e] = pack2((lo16(w4[e]) - mu) * rstd * gg[2 * e] + bt[2 * e], (hi16(w4[e]) - mu) * rstd * gg[2 * e + 1] + bt[2 * e + 1]);
-                mine[c] = make_uint4(o[0], o[1], o[2], o[3]);
+            for (int e = 0; e < 4; ++e) {
+                const float d0 = lo16(w4[e]) - mu, d1 = hi16(w4[e]) - mu;
+                sq += d0 * d0 + d1 * d1;
             }
+        }
+        sq += __shfl_xor(sq, 32, 64);
+        const float rstd = rsqrtf(sq * (1.0f / CI) + a.eps);
+        opaque();
+        const float* shift = a.beta ? a.beta : a.gamma;   // without a shift vector: read the scale again and drop it
+        const bool bon = a.beta != nullptr;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const float4* g4 = reinterpret_cast<const float4*>(a.gamma + 16 * ks + 8 * hf);
+            const float4 ga = g4[0], gb = g4[1];
+            const float4* b4 = reinterpret_cast<const float4*>(shift + 16 * ks + 8 * hf);
+            const float4 ba = b4[0], bb = b4[1];
+            const float gg[8] = {ga.x, ga.y, ga.z, ga.w, gb.x, gb.y, gb.z, gb.w};
+            const float bt[8] = {bon ? ba.x : 0.f, bon ? ba.y : 0.f, bon ? ba.z : 0.f, bon ? ba.w : 0.f,
+                                 bon ? bb.x : 0.f, bon ? bb.y : 0.f, bon ? bb.z : 0.f, bon ? bb.w : 0.f};
+            const uint32_t w4[4] = {xf[ks].u.x, xf[ks].u.y, xf[ks].u.z, xf[ks].u.w};
+            uint32_t o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                o[e] = pack2((lo16(w4[e]) - mu) * rstd * gg[2 * e] + bt[2 * e], (hi16(w4[e]) - mu) * rstd * gg[2 * e + 1] + bt[2 * e + 1]);
+            xf[ks].u = make_uint4(o[0], o[1], o[2], o[3]);
+            if ((ks & 1) == 1) asm volatile("" ::: "memory");   // at most two k-steps of scale/shift loads in flight
         }
     }
+    store_tile(0);
     __syncthreads();
 
-    // ---- Y^T unit by unit. A unit is one 32-column block of the output for RB of the workgroup's four 32-row blocks
-    //      (all four from 128 channels on, so that the workgroup reads every row of W exactly once, from L2, while the
-    //      normalised rows are re-read from LDS; two at 64 channels, where there are too few column blocks to keep four
-    //      waves busy otherwise). Wave w takes units w, w+4, ...
-    //      Row i of the A operand is output column col0 + 16*((i>>2)&1) + 4*(i>>3) + (i&3): with this order the 16
-    //      accumulator registers of a lane are 16 CONSECUTIVE columns of its row (two 16-byte stores), and the two
-    //      half-waves of a row together write 64 contiguous bytes.
-    constexpr int RB = CI == 64 ? 2 : 4;
-    constexpr int UPC = 4 / RB;                              // units per column block
+    // ---- Y^T = W X^T tile by tile: the A operand (32 rows of W) comes from LDS, the B operand is the wave's rows
+    const size_t drow = ok ? (size_t)(a.row_out ? a.row_out[p] : p) : 0;
     const int per_out = a.c_out / a.n_outs;
-    const int units = (a.c_out >> 5) * UPC;
-    const int wcol = 16 * ((l32 >> 2) & 1) + 4 * (l32 >> 3) + (l32 & 3);
-    for (int u = wave; u < units; u += LTH / 64) {
-        const int col0 = (u / UPC) << 5, rb0 = (u % UPC) * RB;
-        f32x16 acc[RB];
+    for (int t = 0; t < n_tiles; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < n_tiles) load_tile(t + 1);
+        const uint16_t* wt = &sw[(size_t)buf * TROWS * PITCH + l32 * PITCH + 8 * hf];
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) acc[rb] = f32x16{0};
-        const uint16_t* wr = a.w + (size_t)(col0 + wcol) * CI + 8 * hf;   // rows of W = output columns
-        const uint16_t* xrow = &sx[(rb0 * 32 + l32) * PITCH + 8 * hf];
-#pragma unroll 2
-        for (int ks = 0; ks < KS; ++ks) {
-            F8 wa;
-            wa.u = *reinterpret_cast<const uint4*>(wr + 16 * ks);
+        for (int cb = 0; cb < TCB; ++cb) {
+            const int col0 = (t * TCB + cb) << 5;
+            if (col0 >= a.c_out) break;
+            f32x16 acc = {0};
+            // W fragments four k-steps at a time, one group ahead of the MFMAs that use them
+            constexpr int G = 4, NG = KS / G;
+            F8 wf[2][G];
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-                F8 xf;
-                xf.u = *reinterpret_cast<const uint4*>(xrow + rb * 32 * PITCH + 16 * ks);
-                acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa.b, xf.b, acc[rb], 0, 0, 0);
+            for (int i = 0; i < G; ++i) wf[0][i].u = *reinterpret_cast<const uint4*>(wt + cb * 32 * PITCH + 16 * i);
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                if (g + 1 < NG) {
+#pragma unroll
+                    for (int i = 0; i < G; ++i)
+                        wf[(g + 1) & 1][i].u = *reinterpret_cast<const uint4*>(wt + cb * 32 * PITCH + 16 * ((g + 1) * G + i));
+                }
+#pragma unroll
+                for (int i = 0; i < G; ++i) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[g & 1][i].b, xf[g * G + i].b, acc, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
-        }
-        const int col = col0 + 16 * hf;                      // first of this lane's 16 columns
-        const int t = col / per_out, lc = col - t * per_out;
-        float bs[16];
+            if (ok) {
+                const int col = col0 + 16 * hf;                      // first of this lane's 16 columns
+                const int to = col / per_out, lc = col - to * per_out;
+                float y[16];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) bs[e] = 0.f;
-        if (a.bias) {
+                for (int e = 0; e < 16; ++e) y[e] = acc[e];
+                if (a.bias) {
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const float4 bv = *reinterpret_cast<const float4*>(a.bias + col + 4 * q4);
-                bs[4 * q4] = bv.x; bs[4 * q4 + 1] = bv.y; bs[4 * q4 + 2] = bv.z; bs[4 * q4 + 3] = bv.w;
-            }
-        }
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            const long long p = row0 + (rb0 + rb) * 32 + l32;    // this lane's row of Y
-            if (p >= a.n) continue;
-            const size_t drow = (size_t)(a.row_out ? a.row_out[p] : p);
-            float y[16];
-#pragma unroll
-            for (int e = 0; e < 16; ++e) y[e] = acc[rb][e] + bs[e];
-            if (a.residual) {
-                const uint4* rp = reinterpret_cast<const uint4*>(a.residual + drow * a.c_out + col);
-#pragma unroll
-                for (int h8 = 0; h8 < 2; ++h8) {
-                    const uint4 rv = rp[h8];
-                    const uint32_t w4[4] = {rv.x, rv.y, rv.z, rv.w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        y[8 * h8 + 2 * e] += lo16(w4[e]);
-                        y[8 * h8 + 2 * e + 1] += hi16(w4[e]);
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const float4 bv = *reinterpret_cast<const float4*>(sbias + col + 4 * q4);
+                        y[4 * q4] += bv.x; y[4 * q4 + 1] += bv.y; y[4 * q4 + 2] += bv.z; y[4 * q4 + 3] += bv.w;
                     }
                 }
-            }
-            uint4* op = reinterpret_cast<uint4*>(a.outs[t] + drow * per_out + lc);
+                if (a.residual) {
+                    const uint4* rp = reinterpret_cast<const uint4*>(a.residual + drow * a.c_out + col);
 #pragma unroll
-            for (int h8 = 0; h8 < 2; ++h8)
-                op[h8] = make_uint4(pack2(y[8 * h8], y[8 * h8 + 1]), pack2(y[8 * h8 + 2], y[8 * h8 + 3]),
-                                    pack2(y[8 * h8 + 4], y[8 * h8 + 5]), pack2(y[8 * h8 + 6], y[8 * h8 + 7]));
+                    for (int h8 = 0; h8 < 2; ++h8) {
+                        const uint4 rv = rp[h8];
+                        const uint32_t w4[4] = {rv.x, rv.y, rv.z, rv.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            y[8 * h8 + 2 * e] += lo16(w4[e]);
+                            y[8 * h8 + 2 * e + 1] += hi16(w4[e]);
+                        }
+                    }
+                }
+                uint4* op = reinterpret_cast<uint4*>(a.outs[to] + drow * per_out + lc);
+#pragma unroll
+                for (int h8 = 0; h8 < 2; ++h8)
+                    op[h8] = make_uint4(pack2(y[8 * h8], y[8 * h8 + 1]), pack2(y[8 * h8 + 2], y[8 * h8 + 3]),
+                                        pack2(y[8 * h8 + 4], y[8 * h8 + 5]), pack2(y[8 * h8 + 6], y[8 * h8 + 7]));
+            }
         }
+        if (t + 1 < n_tiles) store_tile(buf ^ 1);
+        __syncthreads();
     }
 }
 
 template <int CI>
 hipError_t launch_ci(const LinearArgs& a, hipStream_t stream)
 {
-    const size_t lds = (size_t)LBM * (CI + 8) * 2;
+    const unsigned blocks = (unsigned)((a.n + LBM - 1) / LBM);
+    const size_t lds = Tile<CI>::LDS_BYTES + (size_t)a.c_out * 4;
     if (lds > 60000) {
         const hipError_t e = hipFuncSetAttribute((const void*)k_ln_linear<CI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    const unsigned blocks = (unsigned)((a.n + LBM - 1) / LBM);
-    if (blocks > 0) k_ln_linear<CI><<<blocks, LTH, lds, stream>>>(a);
+    if (blocks > 0) k_ln_linear<CI><<<blocks, LTH, Tile<CI>::LDS_BYTES + (size_t)a.c_out * 4, stream>>>(a);
     return hipGetLastError();
 }
 
