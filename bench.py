@@ -124,6 +124,9 @@ def main() -> int:
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "f16"],
                     help="element type of q, k, v and the output: bf16 (the benchmark configurations) or f16 (the "
                          "Appendix's FP16 features; forward path only, not with --pool/--backward/--glue)")
+    ap.add_argument("--bucketize-scale", type=int, default=0, metavar="SCANS",
+                    help="also time f3d_psh_bucketize alone on SCANS uniform-cube scans of 131072 points each (its "
+                         "bandwidth regime: the five configurations are too small to load the memory system)")
     ap.add_argument("--rebalance", action="store_true",
                     help="also time f3d_psh_bucketize with the rebalancing variants: canonical (input-order-independent) "
                          "serving order, seeded probe directions, both")
@@ -277,6 +280,29 @@ def main() -> int:
         res["pool"] = {"rho": rho, "tile": 1024, "op": "mean", "pooled_rows": n_out, "ms": ms, "points_per_s": n / (ms * 1e-3),
                        "roofline": {"bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                                     "frac": gbps / PEAK_HBM_GBPS, "bytes": nbytes}}
+    if args.bucketize_scale > 0:   # the bucketing alone on a batch large enough to be limited by memory traffic
+        big_c, big_bo = wl.many_scans(args.bucketize_scale, 131072, seed=w.seed)
+        nb = int(big_c.shape[0])
+        pb = f3d.make_params(0.05, 1024, 4, args.hash, max_scan_points=131072)
+        cb, bob = torch.from_numpy(big_c).to(dev), torch.from_numpy(big_bo).to(dev)
+        wsb = torch.empty(f3d.workspace_bytes(nb, args.bucketize_scale, pb), dtype=torch.uint8, device=dev)
+        bkb = f3d.psh_bucketize(cb, bob, pb, wsb)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            f3d.psh_bucketize(cb, bob, pb, wsb, bkb)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        gbps = 20.0 * nb / (ms * 1e-3) / 1e9
+        plb = bkb.placed_per_round.cpu().numpy()
+        res["bucketize_scale"] = {"scans": args.bucketize_scale, "points": nb, "ms": ms, "points_per_s": nb / (ms * 1e-3),
+                                  "roofline": {"bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                               "frac": gbps / PEAK_HBM_GBPS, "bytes_per_point": 20},
+                                  "placed_share": {"direct": float(plb[0]) / nb, "probes": float(plb[1:7].sum()) / nb,
+                                                   "recycle": float(plb[7]) / nb}}
+        del cb, bob, wsb, bkb
     if args.rebalance:   # variants of Algorithm 2, outside the headline step
         var = {}
         for name, kw in (("index_axes", {}), ("canonical", {"order": "canonical"}), ("seeded", {"probe_mode": "seeded", "probe_seed": 1}),
