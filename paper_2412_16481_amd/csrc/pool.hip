@@ -16,7 +16,23 @@
 #include "pool.h"
 #include "psh_common.h"
 
+
 namespace f3d {
+
+// The squared distances that decide the nearest sub-bucket are three binary32 products and two binary32 sums, each
+// rounded on its own; a fused multiply-add would round differently and can pick another sub-bucket on a near tie.
+// The compiler contracts a*b + c of ordinary expressions (also through the __fmul_rn / __fadd_rn helpers, which are
+// plain operators), so the products are issued as instructions it cannot look into.
+__device__ __forceinline__ float mul_own_rounding(float x, float y)
+{
+    float r;
+    asm("v_mul_f32_e32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
+    return r;
+}
+__device__ __forceinline__ float dist2(float dx, float dy, float dz)
+{
+    return (mul_own_rounding(dx, dx) + mul_own_rounding(dy, dy)) + mul_own_rounding(dz, dz);
+}
 
 namespace {
 
@@ -285,9 +301,27 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
         if (p < nleft) {
             const int id = left_list[p];
             const float qx = px[id], qy = py[id], qz = pz[id];
-            for (int c = part; c < nopen; c += g) {   // ascending: a tie keeps the lower sub-bucket id
+            // ascending: a tie keeps the lower sub-bucket id. Four candidates per trip, their twelve LDS reads issued
+            // together: the loop is bound by LDS latency, not by arithmetic.
+            int c = part;
+            for (; c + 3 * g < nopen; c += 4 * g) {
+                float cx4[4], cy4[4], cz4[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    cx4[u] = ox[c + u * g];
+                    cy4[u] = oy[c + u * g];
+                    cz4[u] = oz[c + u * g];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float dx = __fsub_rn(qx, cx4[u]), dy = __fsub_rn(qy, cy4[u]), dz = __fsub_rn(qz, cz4[u]);
+                    const float d2 = dist2(dx, dy, dz);
+                    if (bi == 0x7FFFFFFF || d2 < bd) { bd = d2; bi = c + u * g; }
+                }
+            }
+            for (; c < nopen; c += g) {
                 const float dx = __fsub_rn(qx, ox[c]), dy = __fsub_rn(qy, oy[c]), dz = __fsub_rn(qz, oz[c]);
-                const float d2 = __fadd_rn(__fadd_rn(__fmul_rn(dx, dx), __fmul_rn(dy, dy)), __fmul_rn(dz, dz));
+                const float d2 = dist2(dx, dy, dz);
                 if (bi == 0x7FFFFFFF || d2 < bd) { bd = d2; bi = c; }
             }
         }
@@ -361,9 +395,25 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
                 if (tl) {
                     float bd = 0.f;
                     int bj = -1;
-                    for (int c = 0; c < O; ++c) {
+                    int c = 0;
+                    for (; c + 3 < O; c += 4) {   // four candidates per trip, reads first (as in the rounds above)
+                        float cx4[4], cy4[4], cz4[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            cx4[u] = ox[c + u];
+                            cy4[u] = oy[c + u];
+                            cz4[u] = oz[c + u];
+                        }
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const float dx = __fsub_rn(qx0, cx4[u]), dy = __fsub_rn(qy0, cy4[u]), dz = __fsub_rn(qz0, cz4[u]);
+                            const float d2 = dist2(dx, dy, dz);
+                            if (bj < 0 || d2 < bd) { bd = d2; bj = c + u; }
+                        }
+                    }
+                    for (; c < O; ++c) {
                         const float dx = __fsub_rn(qx0, ox[c]), dy = __fsub_rn(qy0, oy[c]), dz = __fsub_rn(qz0, oz[c]);
-                        const float d2 = __fadd_rn(__fadd_rn(__fmul_rn(dx, dx), __fmul_rn(dy, dy)), __fmul_rn(dz, dz));
+                        const float d2 = dist2(dx, dy, dz);
                         if (bj < 0 || d2 < bd) { bd = d2; bj = c; }
                     }
                     mybest = open_list[bj];

@@ -69,7 +69,8 @@ struct ScanCfg {
 
 __device__ __forceinline__ int voxel_of(float c, float mn, float inv)
 {
-    // three separate binary32 operations; the intrinsics forbid contraction into an fma
+    // three separate binary32 operations: subtract, multiply, floor. No product feeds a sum here, so there is nothing
+    // the compiler could contract into a fused multiply-add (the _rn helpers are plain operators and would not stop it).
     float f = floorf(__fmul_rn(__fsub_rn(c, mn), inv));
     int q = f >= (float)F3D_VOXEL_MAX ? F3D_VOXEL_MAX : (int)f;
     return q < 0 ? 0 : q;

@@ -719,6 +719,22 @@ def test_pool_dense_clusters_need_many_rounds():
     check_pool(c, None, feat, None, 1024, 4, 0.5, "xor_div", "sum")
 
 
+def test_pool_near_ties_on_a_lattice():
+    """Points on a lattice of pitch 0.1 (not a binary fraction): very many candidate sub-buckets lie at distances that
+    are equal in exact arithmetic and differ, if at all, in the last bit of the binary32 evaluation. The choice then
+    depends on every product and sum being rounded on its own, in the stated order (a fused multiply-add rounds
+    differently), and on the tie rule."""
+    rng = np.random.default_rng(45)
+    n = 6000
+    ijk = rng.integers(0, 14, (n, 3))
+    c = (ijk * 0.1).astype(np.float32) + np.float32(0.37)
+    c[::7] += (rng.integers(-1, 2, (len(c[::7]), 3)) * np.float32(1e-7)).astype(np.float32)   # and a few one-ulp shifts
+    feat = wl.f32_to_bf16_bits(rng.standard_normal((n, 16)).astype(np.float32))
+    for rho, hash in ((2, "zorder_div"), (3, "xor_mod"), (4, "zorder_mod")):
+        ref = check_pool(c, None, feat, None, 1024, rho, 0.25, hash, "max")
+        assert ref["step_of"].max() >= 3
+
+
 def test_pool_empty_input_and_bad_offsets():
     z = np.zeros((0, 3), np.float32)
     got = f3d.inbucket_pool(dev(z), None, dev(np.zeros((0, 8), np.uint16), torch.bfloat16), None, 1024, 2, 0.1)
