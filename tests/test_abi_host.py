@@ -63,6 +63,10 @@ def test_params_default_and_sizes():
     (dict(n_scans=0), f3d.ERR_INVALID_ARG),
     (dict(n=10_000_000, bucket_cap=64), f3d.ERR_UNSUPPORTED),  # one scan would own > 8192 buckets
     (dict(struct_size=4), f3d.ERR_INVALID_ARG),
+    (dict(order=2), f3d.ERR_INVALID_ARG),
+    (dict(order=-1), f3d.ERR_INVALID_ARG),
+    (dict(probe_mode=3), f3d.ERR_INVALID_ARG),
+    (dict(probe_mode=-1), f3d.ERR_INVALID_ARG),
 ])
 def test_workspace_query_refuses_bad_parameters(kw, code):
     kw = dict(kw)
@@ -76,6 +80,36 @@ def test_workspace_query_refuses_bad_parameters(kw, code):
         p.struct_size = struct_size
     out = ctypes.c_size_t(0)
     assert f3d.lib().f3d_workspace_bytes(n, n_scans, ctypes.byref(p), ctypes.byref(out)) == code
+
+
+def test_rebalancing_variants_in_the_parameter_block():
+    p = f3d.make_params(0.02, 1024)
+    assert (p.order, p.probe_mode, p.probe_seed) == (0, 0, 0) and list(p.probe_table) == [0] * 18
+    q = f3d.make_params(0.02, 1024, order="canonical", probe_mode="table", probe_seed=-1, probe_table=[[1, -2, 3], [4, 5, -6]])
+    assert (q.order, q.probe_mode, q.probe_seed) == (1, 1, 0xFFFFFFFF)
+    assert list(q.probe_table)[:6] == [1, -2, 3, 4, 5, -6]
+    with pytest.raises(ValueError):
+        f3d.make_params(0.02, 1024, probe_table=[[0, 0, 0]] * 7)
+    # the canonical order sorts the points first and needs room for keys, indices and the sorted copy
+    assert f3d.workspace_bytes(200_000, 1, q) > f3d.workspace_bytes(200_000, 1, p) + 200_000 * 48
+
+
+def test_half_precision_attention_refuses_what_the_bfloat16_entry_refuses():
+    L = f3d.lib()
+    fake = 0x10000
+    base = [fake, fake, fake, None, fake, fake, 100, 1, 10, 1024, 4, 0, 2, 2, 4, 16, 0.0, fake, None, None, None]
+    def call(entry, changes):
+        a = list(base)
+        for k, v in changes.items():
+            a[k] = v
+        return entry(*a)
+    for entry in (L.f3d_bucket_swin_attn, L.f3d_bucket_swin_attn_f16):
+        assert call(entry, {15: 24}) == f3d.ERR_UNSUPPORTED        # head_dim
+        assert call(entry, {0: None}) == f3d.ERR_INVALID_ARG       # q
+        assert call(entry, {17: None}) == f3d.ERR_INVALID_ARG      # out
+        assert call(entry, {17: fake + 8}) == f3d.ERR_BAD_ALIGNMENT
+        assert call(entry, {11: 3}) == f3d.ERR_INVALID_ARG         # mode
+        assert call(entry, {6: 0}) == 0                            # an empty input is not an error and launches nothing
 
 
 def test_max_scan_points_lifts_the_bucket_limit():
