@@ -519,6 +519,50 @@ def test_attention_f16_log_sum_exp_and_largest_finite_inputs():
     assert np.abs(got - want_o).max() <= 2.0 ** -9 * 65504.0
 
 
+def test_whole_step_replays_from_a_hip_graph():
+    """The calls launch kernels only (no memset nodes, no allocation, no host synchronisation), so a caller can capture
+    bucketize + attention passes in a HIP graph. Every replay, with eager work and synchronisations in between, must
+    reproduce the eager result bit for bit."""
+    w = wl.make_workload("indoor")
+    n, C = w.n, w.channels
+    coords, bo = dev(w.coords), dev(w.batch_offsets)
+    q, k, v = (dev(a, torch.bfloat16) for a in w.qkv())
+    p = f3d.make_params(w.voxel_size, w.bucket_cap, order="canonical", probe_mode="seeded", probe_seed=3)
+    ws = torch.empty(f3d.workspace_bytes(n, 1, p), dtype=torch.uint8, device=DEV)
+    bk = f3d.psh_bucketize(coords, bo, p, ws)
+    out, back = torch.empty_like(q), torch.empty_like(q)
+    lse = torch.empty(n, w.heads, dtype=torch.float32, device=DEV)
+
+    def step():
+        f3d.psh_bucketize(coords, bo, p, ws, bk)
+        f3d.bucket_swin_attn(q, k, v, bk, w.heads, w.head_dim, "plain", out=out, lse=lse)
+        f3d.bucket_swin_attn(q, k, v, bk, w.heads, w.head_dim, "shift", out=back, original_order=True)
+
+    step()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (bk.perm, bk.inv_perm, bk.offsets, out, back, lse)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                      # warm-up on the capture stream's side
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    torch.cuda.synchronize()
+    for it in range(4):
+        for t in (bk.perm, bk.inv_perm, out, back, lse):
+            t.zero_()                               # eager work between the replays; also proves the replay rewrites all
+        ws.fill_(0x5A + it)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = (bk.perm, bk.inv_perm, bk.offsets, out, back, lse)
+        for a, b in zip(got, want):
+            assert torch.equal(a, b), f"replay {it} differs"
+
+
 # ----------------------------------------------------------------------------- attention backward
 
 
