@@ -6,8 +6,9 @@
 //
 // The sort is a stable least-significant-digit radix sort on 8-bit digits of six 32-bit key words per point, carrying
 // only the point index: per pass one kernel counts the digits of every tile of 2048 positions, and one kernel sums the
-// count rows of the earlier tiles itself (no separate scan launch), ranks its tile by digit in position order (wave
-// ballots over the digit's bits plus per-(round, wave) counters in LDS) and scatters the indices.
+// count rows of the earlier tiles itself (small inputs; from 160 tiles on a third kernel scans the count columns
+// first), ranks its tile by digit in position order (wave ballots over the digit's bits plus per-(round, wave) counters
+// in LDS) and scatters the indices.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -22,6 +23,7 @@ constexpr int OT = 256;          // threads per workgroup
 constexpr int OE = 2048;         // positions per tile
 constexpr int OR = OE / OT;      // rounds: position = tile*OE + round*OT + thread
 constexpr int OW = OT / 64;      // waves
+constexpr int ORDER_SCAN_TILES = 160;
 
 __device__ __forceinline__ int scan_of(const OrderArgs& a, int p)
 {
@@ -120,9 +122,40 @@ __global__ __launch_bounds__(OT) void k_order_count(const int32_t* __restrict__ 
     hist[(size_t)blockIdx.x * 256 + threadIdx.x] = h[threadIdx.x];
 }
 
+// Large inputs only: exclusive prefix over the tiles of every digit's count column, so that the scatter kernel reads one
+// row instead of summing all earlier rows itself. One workgroup per digit; hist[t][d] becomes the number of positions
+// with digit d in the tiles before t, total[d] the count over all tiles.
+__global__ __launch_bounds__(OT) void k_order_scan(uint32_t* __restrict__ hist, uint32_t* __restrict__ total, int tiles)
+{
+    __shared__ uint32_t wsum[OW];
+    const int d = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t carry = 0;
+    for (int t0 = 0; t0 < tiles; t0 += OT) {
+        const int t = t0 + tid;
+        const uint32_t c = t < tiles ? hist[(size_t)t * 256 + d] : 0u;
+        uint32_t inc = c;
+        for (int s = 1; s < 64; s <<= 1) {
+            const uint32_t o = (uint32_t)__shfl_up((int)inc, s, 64);
+            if (lane >= s) inc += o;
+        }
+        if (lane == 63) wsum[wave] = inc;
+        __syncthreads();
+        uint32_t before = 0, all = 0;
+        for (int w = 0; w < OW; ++w) {
+            if (w < wave) before += wsum[w];
+            all += wsum[w];
+        }
+        if (t < tiles) hist[(size_t)t * 256 + d] = carry + before + inc - c;
+        carry += all;
+        __syncthreads();
+    }
+    if (tid == 0) total[d] = carry;
+}
+
 __global__ __launch_bounds__(OT) void k_order_scatter(const int32_t* __restrict__ src, int32_t* __restrict__ dst,
                                                       const uint32_t* __restrict__ word, int shift, int n,
-                                                      const uint32_t* __restrict__ hist, int tiles)
+                                                      const uint32_t* __restrict__ hist, int tiles,
+                                                      const uint32_t* __restrict__ total)
 {
     __shared__ uint32_t base[256];
     __shared__ uint32_t wsum[OW];
@@ -132,11 +165,16 @@ __global__ __launch_bounds__(OT) void k_order_scatter(const int32_t* __restrict_
 
     // first position of digit `tid` for this tile: all smaller digits of all tiles, plus this digit in earlier tiles
     uint32_t pre = 0, tot = 0;
+    if (total) {   // the count columns have been scanned by k_order_scan
+        pre = hist[(size_t)tile * 256 + tid];
+        tot = total[tid];
+    } else {
 #pragma unroll 8
-    for (int t = 0; t < tiles; ++t) {
-        const uint32_t c = hist[(size_t)t * 256 + tid];
-        pre += t < tile ? c : 0u;
-        tot += c;
+        for (int t = 0; t < tiles; ++t) {
+            const uint32_t c = hist[(size_t)t * 256 + tid];
+            pre += t < tile ? c : 0u;
+            tot += c;
+        }
     }
     uint32_t inc = tot;
     for (int d = 1; d < 64; d <<= 1) {
@@ -233,13 +271,17 @@ hipError_t order_launch(const OrderArgs& a, const int32_t** order_out, hipStream
     // least significant first: z, y, x, the code's low and high word (31 bits), the scan (as many digits as it needs)
     const int32_t* src = nullptr;
     int cur = 0;
+    // from this many tiles on a third launch per pass (a scan of the count columns) is cheaper than every workgroup
+    // summing all earlier count rows
+    uint32_t* total = tiles > ORDER_SCAN_TILES ? a.hist + (size_t)tiles * 256 : nullptr;
     const int scan_digits = a.n_scans > 256 ? 2 : (a.n_scans > 1 ? 1 : 0);
     for (int w = 0; w < 6; ++w) {
         const int digits = w < 5 ? 4 : scan_digits;
         const uint32_t* word = a.words + (size_t)w * a.n;
         for (int d = 0; d < digits; ++d) {
             k_order_count<<<tiles, OT, 0, stream>>>(src, word, 8 * d, a.n, a.hist);
-            k_order_scatter<<<tiles, OT, 0, stream>>>(src, a.idx[cur], word, 8 * d, a.n, a.hist, tiles);
+            if (total) k_order_scan<<<256, OT, 0, stream>>>(a.hist, total, tiles);
+            k_order_scatter<<<tiles, OT, 0, stream>>>(src, a.idx[cur], word, 8 * d, a.n, a.hist, tiles, total);
             src = a.idx[cur];
             cur ^= 1;
         }
