@@ -154,7 +154,7 @@ __device__ inline void tile_hash_cfg(int hash, int M, const int* vmax, ScanCfg& 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
-// dynamic LDS, kp = a.kp: px,py,pz [PT] floats | ox,oy,oz [kp] floats | fill [kp] ints | wcnt [PW][kp] u16 |
+// dynamic LDS, kp = a.kp: px,py,pz [PT] floats | o4 [kp] float4 (x, y, z, -) | fill [kp] ints | wcnt [PW][kp] u16 |
 // open_list, id_of_hash, first_idx, ktot [kp] u16 each | members [PT + POOL_MAX_RHO] u16 | pick, rsub, rslot [PT] u16
 __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
 {
@@ -172,10 +172,8 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
     float* px = reinterpret_cast<float*>(smem);
     float* py = px + PT;
     float* pz = py + PT;
-    float* ox = pz + PT;
-    float* oy = ox + kp;
-    float* oz = oy + kp;
-    int* fill = reinterpret_cast<int*>(oz + kp);
+    float4* o4 = reinterpret_cast<float4*>(pz + PT);   // first-row position of every open sub-bucket: one 16-byte read
+    int* fill = reinterpret_cast<int*>(o4 + kp);
     uint16_t* wcnt = reinterpret_cast<uint16_t*>(fill + kp);
     uint16_t* open_list = wcnt + PW * kp;
     uint16_t* id_of_hash = open_list + kp;
@@ -286,9 +284,7 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
         if (open) {
             const int f = first_idx[tid], opos = pre >> 16;
             open_list[opos] = (uint16_t)tid;
-            ox[opos] = px[f];
-            oy[opos] = py[f];
-            oz[opos] = pz[f];
+            o4[opos] = make_float4(px[f], py[f], pz[f], 0.f);
         }
         __syncthreads();
         if (nleft <= 64) break;
@@ -301,28 +297,32 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
         if (p < nleft) {
             const int id = left_list[p];
             const float qx = px[id], qy = py[id], qz = pz[id];
-            // ascending: a tie keeps the lower sub-bucket id. Four candidates per trip, their twelve LDS reads issued
-            // together: the loop is bound by LDS latency, not by arithmetic.
-            int c = part;
-            for (; c + 3 * g < nopen; c += 4 * g) {
-                float cx4[4], cy4[4], cz4[4];
+            // Lane `part` of the row's g lanes takes a contiguous range of the open list, in ascending order: the first
+            // candidate unconditionally, a later one only if strictly nearer (a tie keeps the lower sub-bucket id). Four
+            // candidates per trip, their reads issued together: the loop is bound by instruction issue and LDS latency.
+            const int chunk = (nopen + g - 1) / g;
+            int c = part * chunk;
+            const int cend = min(c + chunk, nopen);
+            if (c < cend) {
+                const float4 o = o4[c];
+                bd = dist2(qx - o.x, qy - o.y, qz - o.z);
+                bi = c;
+                ++c;
+                for (; c + 3 < cend; c += 4) {
+                    float4 v4[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    cx4[u] = ox[c + u * g];
-                    cy4[u] = oy[c + u * g];
-                    cz4[u] = oz[c + u * g];
-                }
+                    for (int u = 0; u < 4; ++u) v4[u] = o4[c + u];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const float dx = __fsub_rn(qx, cx4[u]), dy = __fsub_rn(qy, cy4[u]), dz = __fsub_rn(qz, cz4[u]);
-                    const float d2 = dist2(dx, dy, dz);
-                    if (bi == 0x7FFFFFFF || d2 < bd) { bd = d2; bi = c + u * g; }
+                    for (int u = 0; u < 4; ++u) {
+                        const float d2 = dist2(qx - v4[u].x, qy - v4[u].y, qz - v4[u].z);
+                        if (d2 < bd) { bd = d2; bi = c + u; }
+                    }
                 }
-            }
-            for (; c < nopen; c += g) {
-                const float dx = __fsub_rn(qx, ox[c]), dy = __fsub_rn(qy, oy[c]), dz = __fsub_rn(qz, oz[c]);
-                const float d2 = dist2(dx, dy, dz);
-                if (bi == 0x7FFFFFFF || d2 < bd) { bd = d2; bi = c; }
+                for (; c < cend; ++c) {
+                    const float4 v = o4[c];
+                    const float d2 = dist2(qx - v.x, qy - v.y, qz - v.z);
+                    if (d2 < bd) { bd = d2; bi = c; }
+                }
             }
         }
         for (int d = g >> 1; d >= 1; d >>= 1) {   // smallest distance, the lower list position on a tie
@@ -368,22 +368,18 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
                 for (int base = 0; base < O; base += 64) {
                     const int c = base + lane;
                     int s = 0;
-                    float cx = 0.f, cy = 0.f, cz = 0.f;
+                    float4 co = make_float4(0.f, 0.f, 0.f, 0.f);
                     bool keep = false;
                     if (c < O) {
                         s = open_list[c];
-                        cx = ox[c];
-                        cy = oy[c];
-                        cz = oz[c];
+                        co = o4[c];
                         keep = fill[s] < rho;
                     }
                     const unsigned long long bal = __ballot(keep);
                     if (keep) {
                         const int p = newO + __popcll(bal & lt);
                         open_list[p] = (uint16_t)s;
-                        ox[p] = cx;
-                        oy[p] = cy;
-                        oz[p] = cz;
+                        o4[p] = co;
                     }
                     newO += __popcll(bal);
                 }
@@ -393,28 +389,24 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
                 // nearest open sub-bucket of this lane's row (ascending id: a tie keeps the lower one)
                 int mybest = 0;
                 if (tl) {
-                    float bd = 0.f;
-                    int bj = -1;
-                    int c = 0;
+                    const float4 o = o4[0];   // O > 0: the first candidate unconditionally, later ones if strictly nearer
+                    float bd = dist2(qx0 - o.x, qy0 - o.y, qz0 - o.z);
+                    int bj = 0;
+                    int c = 1;
                     for (; c + 3 < O; c += 4) {   // four candidates per trip, reads first (as in the rounds above)
-                        float cx4[4], cy4[4], cz4[4];
+                        float4 v4[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) v4[u] = o4[c + u];
 #pragma unroll
                         for (int u = 0; u < 4; ++u) {
-                            cx4[u] = ox[c + u];
-                            cy4[u] = oy[c + u];
-                            cz4[u] = oz[c + u];
-                        }
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            const float dx = __fsub_rn(qx0, cx4[u]), dy = __fsub_rn(qy0, cy4[u]), dz = __fsub_rn(qz0, cz4[u]);
-                            const float d2 = dist2(dx, dy, dz);
-                            if (bj < 0 || d2 < bd) { bd = d2; bj = c + u; }
+                            const float d2 = dist2(qx0 - v4[u].x, qy0 - v4[u].y, qz0 - v4[u].z);
+                            if (d2 < bd) { bd = d2; bj = c + u; }
                         }
                     }
                     for (; c < O; ++c) {
-                        const float dx = __fsub_rn(qx0, ox[c]), dy = __fsub_rn(qy0, oy[c]), dz = __fsub_rn(qz0, oz[c]);
-                        const float d2 = dist2(dx, dy, dz);
-                        if (bj < 0 || d2 < bd) { bd = d2; bj = c; }
+                        const float4 v = o4[c];
+                        const float d2 = dist2(qx0 - v.x, qy0 - v.y, qz0 - v.z);
+                        if (d2 < bd) { bd = d2; bj = c; }
                     }
                     mybest = open_list[bj];
                 }
@@ -512,7 +504,7 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
 
 size_t pool_lds_bytes(int kp)
 {
-    return (size_t)3 * PT * 4 + (size_t)3 * kp * 4 + (size_t)kp * 4 + (size_t)PW * kp * 2 + (size_t)4 * kp * 2 +
+    return (size_t)3 * PT * 4 + (size_t)4 * kp * 4 + (size_t)kp * 4 + (size_t)PW * kp * 2 + (size_t)4 * kp * 2 +
            (size_t)(PT + POOL_MAX_RHO) * 2 + (size_t)3 * PT * 2;
 }
 
