@@ -36,48 +36,74 @@ __global__ __launch_bounds__(OT) void k_order_init(OrderArgs a)
     if (i < a.n_scans * 4) a.box[i] = 0xFFFFFFFFu;
 }
 
-// per-scan coordinate minimum (Algorithm 1, "compute voxel coordinate")
+// per-scan coordinate minimum (Algorithm 1, "compute voxel coordinate"). A workgroup takes OB consecutive positions.
+// Almost always they belong to one scan: then the minimum is reduced inside the workgroup and costs three global
+// atomics; a workgroup that straddles a scan boundary publishes wave by wave whenever a wave moves on to another scan.
+constexpr int OB = 4 * OE;
 __global__ __launch_bounds__(OT) void k_order_box(OrderArgs a)
 {
-    const int lane = threadIdx.x & 63;
-    int cur = -1;
+    __shared__ uint32_t red[3];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const long long first = (long long)blockIdx.x * OB;
+    const long long last = min(first + OB, (long long)a.n) - 1;
+    if (first > last) return;
+    const int b_first = scan_of(a, (int)first), b_last = scan_of(a, (int)last);
+    const bool uniform = b_first == b_last;      // offsets are non-decreasing when they are valid at all
+    if (tid < 3) red[tid] = 0xFFFFFFFFu;
+    __syncthreads();
     uint32_t mn[3] = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
-    const auto flush = [&]() {
-        // every lane of the wave arrives here together; lanes with cur < 0 have nothing to give
-        const unsigned long long have = __ballot(cur >= 0);
-        if (!have) return;
-        const int first = __shfl(cur, __ffsll((long long)have) - 1, 64);
-        const bool uniform = __ballot(cur >= 0 && cur != first) == 0;
-        if (uniform) {
-#pragma unroll
-            for (int t = 0; t < 3; ++t) {
-                uint32_t lo = mn[t];
-                for (int d = 32; d >= 1; d >>= 1) lo = min(lo, (uint32_t)__shfl_xor((int)lo, d, 64));
-                if (lane == 0) atomicMin(&a.box[first * 4 + t], lo);
-            }
-        } else if (cur >= 0) {
-#pragma unroll
-            for (int t = 0; t < 3; ++t) atomicMin(&a.box[cur * 4 + t], mn[t]);
-        }
-    };
-#pragma unroll 1
-    for (int r = 0; r < OR; ++r) {
-        const long long e = (long long)blockIdx.x * OE + r * OT + threadIdx.x;
-        const bool ok = e < a.n;
-        const int b = ok ? scan_of(a, (int)e) : -1;
-        // a wave changes scan together or not at all in the common case; any lane that changes flushes the whole wave
-        if (__ballot(ok && cur >= 0 && b != cur)) {
-            flush();
-            cur = -1;
-            mn[0] = mn[1] = mn[2] = 0xFFFFFFFFu;
-        }
-        if (ok) {
-            cur = b;
+    if (uniform) {
+        for (long long e = first + tid; e <= last; e += OT) {
 #pragma unroll
             for (int t = 0; t < 3; ++t) mn[t] = min(mn[t], f2ord(a.coords[(size_t)e * 3 + t]));
         }
+    } else {
+        // a lane walks its positions in increasing order, so its scan index only grows: it keeps the minimum of the
+        // scan it is in; when any lane of the wave moves on to another scan the whole wave publishes (one atomic per
+        // axis if all its lanes were in the same scan, else one per lane and axis)
+        int cur = -1;
+        const auto flush = [&]() {
+            const unsigned long long have = __ballot(cur >= 0);
+            if (!have) return;
+            const int lead = __shfl(cur, __ffsll((long long)have) - 1, 64);
+            if (__ballot(cur >= 0 && cur != lead) == 0) {
+#pragma unroll
+                for (int t = 0; t < 3; ++t) {
+                    uint32_t lo = mn[t];
+                    for (int d = 32; d >= 1; d >>= 1) lo = min(lo, (uint32_t)__shfl_xor((int)lo, d, 64));
+                    if (lane == 0) atomicMin(&a.box[lead * 4 + t], lo);
+                }
+            } else if (cur >= 0) {
+#pragma unroll
+                for (int t = 0; t < 3; ++t) atomicMin(&a.box[cur * 4 + t], mn[t]);
+            }
+        };
+        for (long long e0 = first; e0 <= last; e0 += OT) {   // the trip count is the same for every lane
+            const long long e = e0 + tid;
+            const bool ok = e <= last;
+            const int b = ok ? scan_of(a, (int)e) : -1;
+            if (__ballot(ok && cur >= 0 && b != cur)) {
+                flush();
+                cur = -1;
+                mn[0] = mn[1] = mn[2] = 0xFFFFFFFFu;
+            }
+            if (ok) {
+                cur = b;
+#pragma unroll
+                for (int t = 0; t < 3; ++t) mn[t] = min(mn[t], f2ord(a.coords[(size_t)e * 3 + t]));
+            }
+        }
+        flush();
     }
-    flush();
+    if (!uniform) return;
+#pragma unroll
+    for (int t = 0; t < 3; ++t) {
+        uint32_t lo = mn[t];
+        for (int d = 32; d >= 1; d >>= 1) lo = min(lo, (uint32_t)__shfl_xor((int)lo, d, 64));
+        if (lane == 0) atomicMin(&red[t], lo);
+    }
+    __syncthreads();
+    if (tid < 3) atomicMin(&a.box[b_first * 4 + tid], red[tid]);
 }
 
 // key words of every point
@@ -266,7 +292,7 @@ hipError_t order_launch(const OrderArgs& a, const int32_t** order_out, hipStream
     const int tiles = (a.n + OE - 1) / OE;
     const int blocks = (a.n + OT - 1) / OT;
     k_order_init<<<(a.n_scans * 4 + OT - 1) / OT, OT, 0, stream>>>(a);
-    k_order_box<<<tiles, OT, 0, stream>>>(a);
+    k_order_box<<<(a.n + OB - 1) / OB, OT, 0, stream>>>(a);
     k_order_keys<<<blocks, OT, 0, stream>>>(a);
     // least significant first: z, y, x, the code's low and high word (31 bits), the scan (as many digits as it needs)
     const int32_t* src = nullptr;
