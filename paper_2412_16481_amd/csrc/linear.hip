@@ -61,8 +61,10 @@ __global__ __launch_bounds__(LTH, 3) void k_ln_linear(LinearArgs a)
     constexpr int CPR = CI / 8;                     // 16-byte pieces per row of W
     constexpr int PPT = TROWS * CPR / LTH;          // pieces per thread and tile (4)
     static_assert(TROWS * CPR % LTH == 0, "a W tile is a whole number of pieces per thread");
-    extern __shared__ __attribute__((aligned(16))) uint16_t sw[];   // [2][TROWS][PITCH], then the bias as binary32 [c_out]
-    float* sbias = reinterpret_cast<float*>(sw + 2 * TROWS * PITCH);
+    extern __shared__ __attribute__((aligned(16))) uint16_t sw[];   // [2][TROWS][PITCH], then binary32 bias [c_out], scale [CI], shift [CI]
+    float* sbias = reinterpret_cast<float*>(sw + 2 * TROWS * PITCH);   // [c_out], zeros without a bias
+    float* sgamma = sbias + a.c_out;                                  // [CI] LayerNorm scale
+    float* sbeta = sgamma + CI;                                       // [CI] LayerNorm shift, zeros without one
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hf = lane >> 5;
     const long long p = (long long)blockIdx.x * LBM + wave * 32 + l32;   // this lane's row of Y
@@ -74,29 +76,46 @@ __global__ __launch_bounds__(LTH, 3) void k_ln_linear(LinearArgs a)
     //      stored at slot 8*((j>>2)&3) + 4*(j>>4) + (j&3), so that MFMA row i holds output column
     //      16*((i>>2)&1) + 4*(i>>3) + (i&3) of the block: with this order the 16 accumulator registers of a lane are 16
     //      CONSECUTIVE columns of its row (two 16-byte stores; the two half-waves of a row write 64 contiguous bytes).
-    uint4 wreg[PPT];
-    const auto load_tile = [&](int t) __attribute__((always_inline)) {
+    struct WTile { uint4 v[PPT]; } wreg;   // handled by value: a lambda that captures an array by reference can put it in scratch
+    const auto load_tile = [=](int t) __attribute__((always_inline)) -> WTile {
+        WTile r;
 #pragma unroll
         for (int i = 0; i < PPT; ++i) {
             const int q = tid + i * LTH;
             const int j = q / CPR, c = q % CPR;
-            const int col = t * TROWS + j;
-            wreg[i] = col < a.c_out ? *reinterpret_cast<const uint4*>(a.w + (size_t)col * CI + 8 * c) : make_uint4(0, 0, 0, 0);
+            const int col = min(t * TROWS + j, a.c_out - 1);   // past the last column: some valid row, never used
+            r.v[i] = *reinterpret_cast<const uint4*>(a.w + (size_t)col * CI + 8 * c);
         }
+        return r;
     };
-    const auto store_tile = [&](int buf) __attribute__((always_inline)) {
+    const auto store_tile = [=](int buf, const WTile r) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < PPT; ++i) {
             const int q = tid + i * LTH;
             const int j = q / CPR, c = q % CPR;
             const int jr = j & 31;
             const int slot = (j & ~31) + 8 * ((jr >> 2) & 3) + 4 * (jr >> 4) + (jr & 3);
-            *reinterpret_cast<uint4*>(&sw[(size_t)buf * TROWS * PITCH + slot * PITCH + 8 * c]) = wreg[i];
+            *reinterpret_cast<uint4*>(&sw[(size_t)buf * TROWS * PITCH + slot * PITCH + 8 * c]) = r.v[i];
         }
     };
-    load_tile(0);
-    if (a.bias)   // read by every wave for every tile: kept in LDS, off the vector memory path
-        for (int i = tid; i < a.c_out; i += LTH) sbias[i] = a.bias[i];
+    wreg = load_tile(0);
+    // the output tensors' addresses are kept in LDS: indexing the argument block inside the loop is a dependent load
+    // from memory per tile, in front of the tile's stores
+    __shared__ uint16_t* s_outs[LIN_MAX_OUTS];
+    if (tid == 0) {
+        s_outs[0] = a.outs[0];
+        s_outs[1] = a.outs[1];
+        s_outs[2] = a.outs[2];
+        s_outs[3] = a.outs[3];
+    }
+    // The per-column vectors are read by every wave (the bias for every tile): they are kept in LDS, off the vector
+    // memory path, so that neither the LayerNorm nor an epilogue waits for a trip to memory.
+    for (int i = tid; i < a.c_out; i += LTH) sbias[i] = a.bias ? a.bias[i] : 0.f;
+    if (a.gamma)
+        for (int i = tid; i < CI; i += LTH) {
+            sgamma[i] = a.gamma[i];
+            sbeta[i] = a.beta ? a.beta[i] : 0.f;
+        }
 
     // ---- this lane's part of its row: elements 16*ks + 8*hf .. +7 for every k-step, i.e. the B operand of the MFMAs.
     //      The row stays in registers for the whole kernel.
@@ -105,8 +124,9 @@ __global__ __launch_bounds__(LTH, 3) void k_ln_linear(LinearArgs a)
         const size_t src = ok ? (size_t)(a.row_in ? a.row_in[p] : p) : 0;
         const uint16_t* xr = a.x + src * CI + 8 * hf;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) xf[ks].u = ok ? *reinterpret_cast<const uint4*>(xr + 16 * ks) : make_uint4(0, 0, 0, 0);
+        for (int ks = 0; ks < KS; ++ks) xf[ks].u = *reinterpret_cast<const uint4*>(xr + 16 * ks);   // rows past the end read row 0 and are never stored
     }
+    __syncthreads();   // the vectors are in LDS (the row loads stay in flight across the barrier)
     if (a.gamma) {   // LayerNorm: the two half-waves hold the two halves of a row
         // Between the three passes the packed words are made opaque, so that each pass unpacks them again instead of
         // keeping the whole row alive as binary32 values.
@@ -137,41 +157,57 @@ __global__ __launch_bounds__(LTH, 3) void k_ln_linear(LinearArgs a)
         sq += __shfl_xor(sq, 32, 64);
         const float rstd = rsqrtf(sq * (1.0f / CI) + a.eps);
         opaque();
-        const float* shift = a.beta ? a.beta : a.gamma;   // without a shift vector: read the scale again and drop it
-        const bool bon = a.beta != nullptr;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            const float4* g4 = reinterpret_cast<const float4*>(a.gamma + 16 * ks + 8 * hf);
+            const float4* g4 = reinterpret_cast<const float4*>(sgamma + 16 * ks + 8 * hf);
             const float4 ga = g4[0], gb = g4[1];
-            const float4* b4 = reinterpret_cast<const float4*>(shift + 16 * ks + 8 * hf);
+            const float4* b4 = reinterpret_cast<const float4*>(sbeta + 16 * ks + 8 * hf);
             const float4 ba = b4[0], bb = b4[1];
             const float gg[8] = {ga.x, ga.y, ga.z, ga.w, gb.x, gb.y, gb.z, gb.w};
-            const float bt[8] = {bon ? ba.x : 0.f, bon ? ba.y : 0.f, bon ? ba.z : 0.f, bon ? ba.w : 0.f,
-                                 bon ? bb.x : 0.f, bon ? bb.y : 0.f, bon ? bb.z : 0.f, bon ? bb.w : 0.f};
+            const float bt[8] = {ba.x, ba.y, ba.z, ba.w, bb.x, bb.y, bb.z, bb.w};
             const uint32_t w4[4] = {xf[ks].u.x, xf[ks].u.y, xf[ks].u.z, xf[ks].u.w};
             uint32_t o[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 o[e] = pack2((lo16(w4[e]) - mu) * rstd * gg[2 * e] + bt[2 * e], (hi16(w4[e]) - mu) * rstd * gg[2 * e + 1] + bt[2 * e + 1]);
             xf[ks].u = make_uint4(o[0], o[1], o[2], o[3]);
-            if ((ks & 1) == 1) asm volatile("" ::: "memory");   // at most two k-steps of scale/shift loads in flight
+            if ((ks & 1) == 1) asm volatile("" ::: "memory");   // at most two k-steps of scale/shift reads in flight
         }
     }
-    store_tile(0);
+    store_tile(0, wreg);
     __syncthreads();
 
     // ---- Y^T = W X^T tile by tile: the A operand (32 rows of W) comes from LDS, the B operand is the wave's rows
     const size_t drow = ok ? (size_t)(a.row_out ? a.row_out[p] : p) : 0;
     const int per_out = a.c_out / a.n_outs;
+
     for (int t = 0; t < n_tiles; ++t) {
         const int buf = t & 1;
-        if (t + 1 < n_tiles) load_tile(t + 1);
+        if (t + 1 < n_tiles) wreg = load_tile(t + 1);
         const uint16_t* wt = &sw[(size_t)buf * TROWS * PITCH + l32 * PITCH + 8 * hf];
+        // The next tile goes to LDS in the middle of this iteration: behind enough MFMAs to cover the latency of its
+        // loads, and in front of the stores of the epilogues that follow (the memory counter retires in order, so a
+        // wait placed behind those stores would also wait for them). The other buffer is free: every wave passed the
+        // barrier at the end of the last iteration, after its last read of it.
+        bool staged = t + 1 >= n_tiles;
 #pragma unroll
         for (int cb = 0; cb < TCB; ++cb) {
             const int col0 = (t * TCB + cb) << 5;
             if (col0 >= a.c_out) break;
             f32x16 acc = {0};
+            // what the epilogue needs from LDS is requested before the MFMAs, not behind them
+            const int col = col0 + 16 * hf;                      // first of this lane's 16 columns
+            const int to = col / per_out, lc = col - to * per_out;
+            uint16_t* const ob = s_outs[to];
+            float4 bv[4];
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) bv[q4] = *reinterpret_cast<const float4*>(sbias + col + 4 * q4);
+            uint4 rv[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};   // the residual's 16 columns (bf16 zeros without one)
+            if (a.residual) {
+                const uint4* rp = reinterpret_cast<const uint4*>(a.residual + drow * a.c_out + col);   // drow is a valid row also past the end
+                rv[0] = rp[0];
+                rv[1] = rp[1];
+            }
             // W fragments four k-steps at a time, one group ahead of the MFMAs that use them
             constexpr int G = 4, NG = KS / G;
             F8 wf[2][G];
@@ -188,40 +224,36 @@ __global__ __launch_bounds__(LTH, 3) void k_ln_linear(LinearArgs a)
                 for (int i = 0; i < G; ++i) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[g & 1][i].b, xf[g * G + i].b, acc, 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
+            if (cb == TCB / 2 && !staged) {
+                store_tile(buf ^ 1, wreg);
+                staged = true;
+            }
             if (ok) {
-                const int col = col0 + 16 * hf;                      // first of this lane's 16 columns
-                const int to = col / per_out, lc = col - to * per_out;
                 float y[16];
 #pragma unroll
-                for (int e = 0; e < 16; ++e) y[e] = acc[e];
-                if (a.bias) {
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    y[4 * q4] = acc[4 * q4] + bv[q4].x;
+                    y[4 * q4 + 1] = acc[4 * q4 + 1] + bv[q4].y;
+                    y[4 * q4 + 2] = acc[4 * q4 + 2] + bv[q4].z;
+                    y[4 * q4 + 3] = acc[4 * q4 + 3] + bv[q4].w;
+                }
 #pragma unroll
-                    for (int q4 = 0; q4 < 4; ++q4) {
-                        const float4 bv = *reinterpret_cast<const float4*>(sbias + col + 4 * q4);
-                        y[4 * q4] += bv.x; y[4 * q4 + 1] += bv.y; y[4 * q4 + 2] += bv.z; y[4 * q4 + 3] += bv.w;
+                for (int h8 = 0; h8 < 2; ++h8) {
+                    const uint32_t w4[4] = {rv[h8].x, rv[h8].y, rv[h8].z, rv[h8].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        y[8 * h8 + 2 * e] += lo16(w4[e]);
+                        y[8 * h8 + 2 * e + 1] += hi16(w4[e]);
                     }
                 }
-                if (a.residual) {
-                    const uint4* rp = reinterpret_cast<const uint4*>(a.residual + drow * a.c_out + col);
-#pragma unroll
-                    for (int h8 = 0; h8 < 2; ++h8) {
-                        const uint4 rv = rp[h8];
-                        const uint32_t w4[4] = {rv.x, rv.y, rv.z, rv.w};
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            y[8 * h8 + 2 * e] += lo16(w4[e]);
-                            y[8 * h8 + 2 * e + 1] += hi16(w4[e]);
-                        }
-                    }
-                }
-                uint4* op = reinterpret_cast<uint4*>(a.outs[to] + drow * per_out + lc);
+                uint4* op = reinterpret_cast<uint4*>(ob + drow * per_out + lc);
 #pragma unroll
                 for (int h8 = 0; h8 < 2; ++h8)
                     op[h8] = make_uint4(pack2(y[8 * h8], y[8 * h8 + 1]), pack2(y[8 * h8 + 2], y[8 * h8 + 3]),
                                         pack2(y[8 * h8 + 4], y[8 * h8 + 5]), pack2(y[8 * h8 + 6], y[8 * h8 + 7]));
             }
         }
-        if (t + 1 < n_tiles) store_tile(buf ^ 1);
+        if (!staged) store_tile(buf ^ 1, wreg);   // a last, partial tile ended before the staging point
         __syncthreads();
     }
 }
@@ -230,12 +262,12 @@ template <int CI>
 hipError_t launch_ci(const LinearArgs& a, hipStream_t stream)
 {
     const unsigned blocks = (unsigned)((a.n + LBM - 1) / LBM);
-    const size_t lds = Tile<CI>::LDS_BYTES + (size_t)a.c_out * 4;
+    const size_t lds = Tile<CI>::LDS_BYTES + (size_t)a.c_out * 4 + (size_t)2 * CI * 4;
     if (lds > 60000) {
         const hipError_t e = hipFuncSetAttribute((const void*)k_ln_linear<CI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    if (blocks > 0) k_ln_linear<CI><<<blocks, LTH, Tile<CI>::LDS_BYTES + (size_t)a.c_out * 4, stream>>>(a);
+    if (blocks > 0) k_ln_linear<CI><<<blocks, LTH, lds, stream>>>(a);
     return hipGetLastError();
 }
 
