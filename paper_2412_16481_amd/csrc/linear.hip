@@ -98,6 +98,9 @@ __global__ __launch_bounds__(LTH, 3) void k_ln_linear(LinearArgs a)
             *reinterpret_cast<uint4*>(&sw[(size_t)buf * TROWS * PITCH + slot * PITCH + 8 * c]) = r.v[i];
         }
     };
+    // Everything the prologue reads from memory is requested before anything waits: the row index (the row loads depend
+    // on it), the first W tile, the per-column vectors, then the rows themselves.
+    const size_t src = ok ? (size_t)(a.row_in ? a.row_in[p] : p) : 0;
     wreg = load_tile(0);
     // the output tensors' addresses are kept in LDS: indexing the argument block inside the loop is a dependent load
     // from memory per tile, in front of the tile's stores
@@ -109,22 +112,37 @@ __global__ __launch_bounds__(LTH, 3) void k_ln_linear(LinearArgs a)
         s_outs[3] = a.outs[3];
     }
     // The per-column vectors are read by every wave (the bias for every tile): they are kept in LDS, off the vector
-    // memory path, so that neither the LayerNorm nor an epilogue waits for a trip to memory.
-    for (int i = tid; i < a.c_out; i += LTH) sbias[i] = a.bias ? a.bias[i] : 0.f;
-    if (a.gamma)
-        for (int i = tid; i < CI; i += LTH) {
-            sgamma[i] = a.gamma[i];
-            sbeta[i] = a.beta ? a.beta[i] : 0.f;
+    // memory path, so that neither the LayerNorm nor an epilogue waits for a trip to memory. Loads in batches of four
+    // without per-element predicates (an index past the end re-reads the last element and is not written).
+    float gv = 0.f, bev = 0.f;
+    if (a.gamma) {
+        gv = a.gamma[min(tid, CI - 1)];
+        if (a.beta) bev = a.beta[min(tid, CI - 1)];
+    }
+    if (a.bias) {
+        for (int i0 = tid; i0 < a.c_out; i0 += 4 * LTH) {
+            float v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = a.bias[min(i0 + u * LTH, a.c_out - 1)];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (i0 + u * LTH < a.c_out) sbias[i0 + u * LTH] = v[u];
         }
+    } else {
+        for (int i = tid; i < a.c_out; i += LTH) sbias[i] = 0.f;
+    }
 
     // ---- this lane's part of its row: elements 16*ks + 8*hf .. +7 for every k-step, i.e. the B operand of the MFMAs.
     //      The row stays in registers for the whole kernel.
     F8 xf[KS];
     {
-        const size_t src = ok ? (size_t)(a.row_in ? a.row_in[p] : p) : 0;
         const uint16_t* xr = a.x + src * CI + 8 * hf;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) xf[ks].u = *reinterpret_cast<const uint4*>(xr + 16 * ks);   // rows past the end read row 0 and are never stored
+    }
+    if (a.gamma && tid < CI) {
+        sgamma[tid] = gv;
+        sbeta[tid] = bev;
     }
     __syncthreads();   // the vectors are in LDS (the row loads stay in flight across the barrier)
     if (a.gamma) {   // LayerNorm: the two half-waves hold the two halves of a row
