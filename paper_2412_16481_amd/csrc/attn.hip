@@ -140,22 +140,6 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
     const size_t hoff = (size_t)head * D;
     const uint32_t row_bytes = (uint32_t)a.C * 2u;
 
-    // ---- this lane's query fragments: row l32 of each of the wave's QT query tiles, dims 8*hf + 16*ks ..
-    U4 qf[QT][KS];
-    int orow[QT];
-#pragma unroll
-    for (int t = 0; t < QT; ++t) {
-        const int xq = qb * BM + (wave * QT + t) * 32 + l32;
-        const bool ok = xq < ng;
-        orow[t] = ok ? seg_row(xq) : -1;
-        const size_t gr = ok ? (size_t)(a.perm ? a.perm[orow[t]] : orow[t]) : 0;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            qf[t][ks].u = make_uint4(0, 0, 0, 0);
-            if (ok) qf[t][ks].u = *reinterpret_cast<const uint4*>(a.q + gr * a.C + hoff + ks * 16 + hf * 8);
-        }
-    }
-
     // ---- staging of K and V rows. The row index of a staged key goes through the permutation, a load the
     //      K/V loads depend on; it is fetched one stage earlier than the rows themselves so that no stage
     //      starts with a dependent round trip to memory. Positions past the end of the scope fetch its last
@@ -213,6 +197,29 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
         }
     };
 
+    // ---- the first memory requests of the workgroup, in the order that makes two round trips of them instead of
+    //      four: the row indices (of the queries and of the keys of stage 0, both through the permutation), then the
+    //      query fragments and the K/V rows of stage 0. The query fragment is row l32 of each of the wave's QT query
+    //      tiles, dims 8*hf + 16*ks ..
+    U4 qf[QT][KS];
+    int orow[QT];
+    size_t qrow[QT];
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+        const int xq = qb * BM + (wave * QT + t) * 32 + l32;
+        orow[t] = xq < ng ? seg_row(xq) : -1;
+        const int r = max(orow[t], 0);                       // past the end: some valid row, never stored
+        qrow[t] = (size_t)(a.perm ? a.perm[r] : r);
+    }
+    fetch_rows(0);
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            qf[t][ks].u = *reinterpret_cast<const uint4*>(a.q + qrow[t] * a.C + hoff + ks * 16 + hf * 8);
+    }
+    load_stage();
+
     // head_dim 16: rows 16 and 17 of V^T are constants (ones -> softmax denominator, zeros -> unused rows)
     if (D == 16) {
         for (int i = tid; i < 2 * VSTR; i += 256) {
@@ -264,7 +271,7 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
     // afterwards; scores beyond about +-55 (natural log units) fail the check and the workgroup repeats the
     // sweep with ROBUST == true, the usual running-maximum form.
     auto sweep = [&](auto robust_tag) {
-        constexpr bool ROBUST = decltype(robust_tag)::value;
+        constexpr bool ROBUST = decltype(robust_tag)::value;   // the optimistic sweep finds stage 0 already requested
         float m_ref[QT];
         bool first[QT];
 #pragma unroll
@@ -274,8 +281,10 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
             m_ref[t] = 0.f;
             first[t] = true;
         }
-        fetch_rows(0);
-        load_stage();
+        if (ROBUST) {
+            fetch_rows(0);
+            load_stage();
+        }
         if (nst > 1) fetch_rows(1);
         store_stage(0);
         __syncthreads();
