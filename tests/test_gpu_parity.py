@@ -385,6 +385,26 @@ def test_attention_large_logits_stay_finite():
     attn_case(q, k, v, bk, ref, 2, 16, "plain", True)
 
 
+def test_attention_large_values_meet_the_relative_bound():
+    """Values of magnitude up to about 12 and a peaked softmax (scale 1): outputs are then near single V rows and the
+    absolute 1e-2 no longer covers the bf16 rounding of the output itself (2^-9 |o|), nor that of the probabilities
+    (2^-9 relative each, worth up to 2^-9 max|v| when one key dominates). Bound: 1.25 * 2^-8 * max|v| element by element."""
+    bk, ref, n = hand_layout([[64, 64, 64, 50, 64, 64, 9], [64, 3]], 256, 4)
+    rng = np.random.default_rng(36)
+    for d, heads in ((16, 3), (32, 2)):
+        q, k, v = (wl.f32_to_bf16_bits((rng.standard_normal((n, heads * d)) * 3.0).astype(np.float32)) for _ in range(3))
+        bound = 1.25 * 2.0 ** -8 * float(np.abs(wl.bf16_bits_to_f32(v)).max())
+        for mode in ("plain", "shift", "stride"):
+            out = f3d.bucket_swin_attn(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), bk, heads, d, mode,
+                                       2, 2, True, 1.0)
+            torch.cuda.synchronize()
+            want = oracle.attn(q, k, v, ref["perm"], ref["offsets"], ref["scan_bucket_start"], 4, mode, heads, d, 2, 2, 1.0)
+            got = out.float().cpu().numpy().astype(np.float64)
+            assert np.isfinite(got).all()
+            assert np.abs(got - want).max() <= bound
+            assert np.abs(want).max() > 4.0   # the case is what it claims to be
+
+
 def test_attention_closed_forms_on_gpu():
     bk, ref, n = hand_layout([[64] * 7 + [30]], 256, 4)
     rng = np.random.default_rng(35)
