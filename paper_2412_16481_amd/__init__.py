@@ -132,8 +132,10 @@ def make_params(voxel_size: float, bucket_cap: int, scope_buckets: int = 4, hash
 
 def max_buckets(n: int, n_scans: int, params: f3d_params) -> int:
     r = int(lib().f3d_max_buckets(n, n_scans, ctypes.byref(params)))
-    if r < 0:
-        raise Flash3DError(ERR_INVALID_ARG, "f3d_max_buckets")
+    if r < 0:   # the call itself only says "refused"; the size query on the same arguments names the reason
+        out = ctypes.c_size_t(0)
+        rc = lib().f3d_workspace_bytes(n, n_scans, ctypes.byref(params), ctypes.byref(out))
+        raise Flash3DError(rc if rc != F3D_OK else ERR_INVALID_ARG, "f3d_max_buckets")
     return r
 
 

@@ -344,8 +344,10 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
                         // tile sets it): exponentials stay below 256 and O is rescaled rarely
                         if (first[t] || __builtin_amdgcn_ballot_w64(mx > m_ref[t] + 8.0f)) {
                             const float m_new = first[t] ? mx : fmaxf(mx, m_ref[t]);
+                            // the first tile has nothing to rescale (O and the sum are zero), and 2^(0 - m_new) would be
+                            // infinite for a maximum below -128: 0 * inf
+                            const float alpha = first[t] ? 1.0f : __builtin_amdgcn_exp2f(m_ref[t] - m_new);
                             first[t] = false;
-                            const float alpha = __builtin_amdgcn_exp2f(m_ref[t] - m_new);
                             m_ref[t] = m_new;
                             constexpr int NO = (D == 16) ? 9 : 16;
 #pragma unroll

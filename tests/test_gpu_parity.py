@@ -385,6 +385,23 @@ def test_attention_large_logits_stay_finite():
     attn_case(q, k, v, bk, ref, 2, 16, "plain", True)
 
 
+@pytest.mark.parametrize("d", [16, 32])
+def test_attention_every_score_far_below_zero(d):
+    """All scores of a scope near -370 in log2 units (q = +8, k = -8 and a little noise): the sweep against the fixed
+    reference underflows, the running-maximum sweep takes over, and its first tile meets a maximum below -128. The
+    softmax is that of the small differences between the scores."""
+    bk, ref, n = hand_layout([[2], [40], [64, 64, 3], [1]], 256, 4)
+    rng = np.random.default_rng(37)
+    heads = 2
+    q = wl.f32_to_bf16_bits(np.full((n, heads * d), 8.0, np.float32))
+    k = wl.f32_to_bf16_bits((-8.0 + 0.25 * rng.standard_normal((n, heads * d))).astype(np.float32))
+    v = wl.f32_to_bf16_bits(rng.standard_normal((n, heads * d)).astype(np.float32))
+    for mode in ("plain", "shift"):
+        attn_case(q, k, v, bk, ref, heads, d, mode, True, scale=0.25)
+    attn_case_f16(wl.bf16_bits_to_f32(q).astype(np.float16), wl.bf16_bits_to_f32(k).astype(np.float16),
+                  wl.bf16_bits_to_f32(v).astype(np.float16), bk, ref, heads, d, "plain", True, scale=0.25)
+
+
 def test_attention_large_values_meet_the_relative_bound():
     """Values of magnitude up to about 12 and a peaked softmax (scale 1): outputs are then near single V rows and the
     absolute 1e-2 no longer covers the bf16 rounding of the output itself (2^-9 |o|), nor that of the probabilities
@@ -588,8 +605,12 @@ def test_whole_step_replays_from_a_hip_graph():
 
 def bwd_case(q, k, v, g, bk, ref_layout, heads, d, mode, use_perm, scope_sel=None, shift=2, stride=2):
     """Forward (with log-sum-exp) and backward on the GPU against the binary64 gradient of the oracle.
-    Bound: 8e-3 * max(1, max|gradient|) per tensor: the bf16 rounding of the stored gradient is up to 2^-9 relative
-    (4.7e-3 at |g| = 2.4), the bf16 roundings of P and dS and of the forward output inside D add about 1e-3."""
+    Bound per element: 2^-8 |g| for the bf16 rounding of the stored gradient itself (half a spacing at the bottom of a
+    binade), plus 7e-3 * max(1, max|gradient|) for the rest: D is the row sum of dO * O taken from the STORED bf16 output
+    (FlashAttention-2's backward), so it carries about 2^-9 |o| |dO| sqrt(d) (up to 0.02 in the tails), an error common to
+    all keys of a row that enters dQ as scale * dD * |sum_j P_j k_j| (up to 0.012 in a scope of a few rows with a peaked
+    softmax); the bf16 roundings of P and dS add about 2^-9 of the sum of the terms' magnitudes. The mean stays below
+    6e-4 * max(1, max|gradient|)."""
     n = q.shape[0]
     tq, tk, tv, tg = (dev(x, torch.bfloat16) for x in (q, k, v, g))
     lse = torch.empty(n, heads, dtype=torch.float32, device=DEV)
@@ -605,7 +626,8 @@ def bwd_case(q, k, v, g, bk, ref_layout, heads, d, mode, use_perm, scope_sel=Non
         assert np.isfinite(gg).all()
         err = np.abs(gg[rows] - want[name][rows])
         top = max(1.0, float(np.abs(want[name][rows]).max()))
-        assert err.max() <= 8e-3 * top, f"{name}: max-abs {err.max():.4g} > {8e-3 * top:.4g}"
+        bound = 2.0 ** -8 * np.abs(want[name][rows]) + 7e-3 * top
+        assert (err <= bound).all(), f"{name}: largest excess {(err - bound).max():.4g} (max-abs {err.max():.4g}, top {top:.4g})"
         assert err.mean() <= 6e-4 * top
     return grads
 
