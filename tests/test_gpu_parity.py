@@ -902,3 +902,73 @@ def test_ln_linear_edge_sizes_and_block_composition():
     bits = lambda t_: t_.view(torch.int16).cpu().numpy().view(np.uint16)
     want = oracle.attn(bits(q), bits(k), bits(v), None, ref["offsets"], ref["scan_bucket_start"], 4, "shift", w_.heads, w_.head_dim)
     assert np.abs(out.float().cpu().numpy() - want).max() <= ATOL
+
+
+# ----------------------------------------------------------------------------- random configurations
+
+
+def random_cloud(rng, n, kind):
+    if kind == 0:
+        return (rng.random((n, 3)) * rng.uniform(0.5, 30)).astype(np.float32)
+    if kind == 1:
+        return clustered_cloud(rng, n)
+    if kind == 2:   # a lattice: many coincident points
+        return (rng.integers(0, rng.integers(2, 40), (n, 3)) * 0.1).astype(np.float32)
+    if kind == 3:   # far from the origin: the spacing of binary32 exceeds small voxels
+        return (rng.random((n, 3)) * 20 + rng.choice([-1e6, 1e5, 3e4])).astype(np.float32)
+    if kind == 4:   # a line along one axis, negative coordinates
+        c = np.zeros((n, 3), np.float32)
+        c[:, int(rng.integers(0, 3))] = -rng.random(n) * 50
+        return c
+    return np.tile(rng.random((1, 3)).astype(np.float32) * 5, (n, 1))   # every point the same
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_configurations_of_every_entry_point(seed):
+    """A configuration drawn from the whole parameter space of the calls (sizes, ragged and empty scans, cloud shape,
+    hash, probes, order, schedule, scope shape, pass mode, heads, element type, pooling and glue shapes), every entry
+    point against the oracle under the bounds of the tests above."""
+    rng = np.random.default_rng(7000 + seed)
+    n_scans = int(rng.choice([1, 2, 5, 60]))
+    n = int(rng.integers(n_scans, 200 * n_scans if n_scans == 60 else 7000))
+    bo = np.concatenate([[0], np.sort(rng.integers(0, n + 1, n_scans - 1)), [n]]).astype(np.int32)
+    kind = int(rng.integers(0, 6))
+    coords = np.concatenate([random_cloud(rng, int(bo[i + 1] - bo[i]), kind) + 3.0 * i for i in range(n_scans)]).reshape(n, 3)
+    m = int(rng.choice([1, 2, 3, 4, 8, 16]))
+    cap = 16 * m * int(rng.choice([1, 2, 4, 8, 16]))
+    kw = {"order": str(rng.choice(["index", "index", "canonical"])), "schedule": str(rng.choice(["auto", "general"])),
+          "probe_mode": str(rng.choice(["axes", "axes", "seeded", "table"])), "probe_seed": int(rng.integers(0, 2 ** 31)),
+          "probe_table": rng.integers(-5, 6, (6, 3)).tolist(), "max_scan_points": int(np.diff(bo).max())}
+    if rng.random() < 0.2:
+        kw["div"] = int(rng.integers(1, 5000))
+    bk, ref = check_bucketize(coords, bo, float(rng.choice([1e-6, 0.01, 0.05, 0.5, 7.0])), cap, m, str(rng.choice(HASHES)),
+                              int(rng.choice([0, 1, 3, 6, 6])), **kw)
+
+    heads, d = int(rng.choice([1, 2, 3, 8])), int(rng.choice([16, 32]))
+    mode = str(rng.choice(["plain", "shift", "stride"])) if m > 1 else str(rng.choice(["plain", "stride"]))
+    shift, stride = (int(rng.integers(1, m)) if m > 1 else 1), int(rng.integers(1, 6))
+    use_perm, scale = bool(rng.random() < 0.5), float(rng.choice([0.0, 0.1]))
+    q, k, v, g = (wl.f32_to_bf16_bits(rng.standard_normal((n, heads * d)).astype(np.float32)) for _ in range(4))
+    attn_case(q, k, v, bk, ref, heads, d, mode, use_perm, None, shift, stride, scale)
+    qh, kh, vh = (wl.bf16_bits_to_f32(x).astype(np.float16) for x in (q, k, v))
+    attn_case_f16(qh, kh, vh, bk, ref, heads, d, mode, use_perm, None, shift, stride, scale)
+    grads = bwd_case(q, k, v, g, bk, ref, heads, d, mode, use_perm, None, shift, stride)
+    # the same results in input order, from the kernels' own stores
+    tq, tk, tv, tg = (dev(x, torch.bfloat16) for x in (q, k, v, g))
+    lse = torch.empty(n, heads, dtype=torch.float32, device=DEV)
+    out_bm = f3d.bucket_swin_attn(tq, tk, tv, bk, heads, d, mode, shift, stride, use_perm, lse=lse)
+    out_in = f3d.bucket_swin_attn(tq, tk, tv, bk, heads, d, mode, shift, stride, use_perm, original_order=True)
+    g_in = f3d.bucket_swin_attn_bwd(tq, tk, tv, out_bm, tg, lse, bk, heads, d, mode, shift, stride, use_perm, original_order=True)
+    torch.cuda.synchronize()
+    assert torch.equal(f3d.unpermute(out_bm, bk.perm).view(torch.int16), out_in.view(torch.int16))
+    for a_, b_ in zip(grads, g_in):
+        assert torch.equal(f3d.unpermute(a_, bk.perm).view(torch.int16), b_.view(torch.int16))
+
+    feat = wl.f32_to_bf16_bits(rng.standard_normal((n, int(rng.choice([8, 16, 64, 128])))).astype(np.float32))
+    check_pool(coords, ref["perm"], feat, bo, int(rng.choice([1, 7, 64, 100, 512, 1000, 1024])), int(rng.choice([1, 2, 3, 4, 8, 33, 64])),
+               float(rng.choice([0.02, 0.1, 0.5])), str(rng.choice(HASHES)), str(rng.choice(["sum", "mean", "min", "max"])))
+
+    c_in, n_outs = int(rng.choice([64, 128, 256])), int(rng.choice([1, 2, 3]))
+    c_out = 64 * n_outs * int(rng.choice([1, 2, 4]))
+    check_ln_linear(n, c_in, c_out, n_outs, rng, ln=bool(rng.random() < 0.6), with_bias=bool(rng.random() < 0.7),
+                    with_res=bool(rng.random() < 0.5), gather=bool(rng.random() < 0.5), scatter=bool(rng.random() < 0.5))
