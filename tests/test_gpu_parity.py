@@ -972,3 +972,30 @@ def test_random_configurations_of_every_entry_point(seed):
     c_out = 64 * n_outs * int(rng.choice([1, 2, 4]))
     check_ln_linear(n, c_in, c_out, n_outs, rng, ln=bool(rng.random() < 0.6), with_bias=bool(rng.random() < 0.7),
                     with_res=bool(rng.random() < 0.5), gather=bool(rng.random() < 0.5), scatter=bool(rng.random() < 0.5))
+
+
+def test_calls_on_two_streams_do_not_share_state():
+    """The library keeps no state between calls: two different jobs enqueued alternately on two streams, each with
+    its own buffers, give exactly what each gives alone."""
+    wa, wb = wl.make_workload("tiny"), wl.make_workload("indoor")
+    jobs = []
+    for w, hash_ in ((wa, "xor_mod"), (wb, "zorder_div")):
+        p = f3d.make_params(w.voxel_size, w.bucket_cap, w.scope_buckets, hash_)
+        coords, bo = dev(w.coords), dev(w.batch_offsets.astype(np.int32))
+        q, k, v = (dev(x, torch.bfloat16) for x in w.qkv())
+        alone = f3d.psh_bucketize(coords, bo, p)
+        out_alone = f3d.bucket_swin_attn(q, k, v, alone, w.heads, w.head_dim, "shift")
+        torch.cuda.synchronize()
+        ws = torch.empty(f3d.workspace_bytes(w.n, w.n_scans, p), dtype=torch.uint8, device=DEV)
+        jobs.append((w, p, coords, bo, q, k, v, alone, out_alone, ws, torch.cuda.Stream()))
+    results = [[], []]
+    for rep in range(3):
+        for j, (w, p, coords, bo, q, k, v, alone, out_alone, ws, stream) in enumerate(jobs):
+            with torch.cuda.stream(stream):
+                bk = f3d.psh_bucketize(coords, bo, p, ws)
+                results[j].append((bk, f3d.bucket_swin_attn(q, k, v, bk, w.heads, w.head_dim, "shift")))
+    torch.cuda.synchronize()
+    for j, (w, p, coords, bo, q, k, v, alone, out_alone, ws, stream) in enumerate(jobs):
+        for bk, out in results[j]:
+            assert torch.equal(bk.perm, alone.perm) and torch.equal(bk.offsets, alone.offsets)
+            assert torch.equal(out.view(torch.int16), out_alone.view(torch.int16))
