@@ -151,6 +151,22 @@ def _ptr(t) -> Optional[int]:
     return None if t is None else t.data_ptr()
 
 
+def _need(t, name: str, dtype, shape=None, optional: bool = False):
+    """The C ABI sees only addresses: a tensor of the wrong type, shape or device would be read or written out of
+    bounds. Refuse it here, with its name. `shape` entries of None are not checked."""
+    if t is None:
+        if optional:
+            return
+        raise ValueError(f"{name} is required")
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous CUDA tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must have dtype {dtype}, not {t.dtype}")
+    if shape is not None:
+        if t.dim() != len(shape) or any(w is not None and int(g) != int(w) for g, w in zip(t.shape, shape)):
+            raise ValueError(f"{name} must have shape {tuple(shape)}, not {tuple(t.shape)}")
+
+
 def _stream() -> int:
     import torch
     return torch.cuda.current_stream().cuda_stream
@@ -171,14 +187,22 @@ class Buckets:
     max_buckets: int = 0
 
 
+def _check_buckets(b: "Buckets", needs_perm: bool) -> None:
+    import torch
+    _need(b.offsets, "buckets.offsets", torch.int32, (None,))
+    if int(b.offsets.shape[0]) < b.max_buckets + 1:
+        raise ValueError("buckets.offsets is shorter than max_buckets + 1")
+    _need(b.scan_bucket_start, "buckets.scan_bucket_start", torch.int32, (b.n_scans + 1,))
+    _need(b.perm, "buckets.perm", torch.int32, (b.n,), optional=not needs_perm)
+
+
 def psh_bucketize(coords, batch_offsets, params: f3d_params, workspace=None, out: Optional[Buckets] = None) -> Buckets:
     """f3d_psh_bucketize on torch CUDA tensors. coords: float32 [n,3]; batch_offsets: int32 [n_scans+1] or None."""
     import torch
-    assert coords.is_cuda and coords.dtype == torch.float32 and coords.is_contiguous()
+    _need(coords, "coords", torch.float32, (None, 3))
     n = int(coords.shape[0])
+    _need(batch_offsets, "batch_offsets", torch.int32, (None,), optional=True)
     n_scans = 1 if batch_offsets is None else int(batch_offsets.shape[0]) - 1
-    if batch_offsets is not None:
-        assert batch_offsets.is_cuda and batch_offsets.dtype == torch.int32 and batch_offsets.is_contiguous()
     dev = coords.device
     if out is None:
         kmax = max_buckets(n, n_scans, params)
@@ -186,8 +210,17 @@ def psh_bucketize(coords, batch_offsets, params: f3d_params, workspace=None, out
                       torch.empty(kmax + 1, dtype=torch.int32, device=dev),
                       torch.empty(n_scans + 1, dtype=torch.int32, device=dev),
                       torch.empty(8, dtype=torch.int32, device=dev), n, n_scans, params.bucket_cap, params.scope_buckets, kmax)
+    else:
+        if out.n != n or out.n_scans != n_scans:
+            raise ValueError("`out` was made for another input size")
+        _need(out.perm, "out.perm", torch.int32, (n,))
+        _need(out.inv_perm, "out.inv_perm", torch.int32, (n,), optional=True)
+        _need(out.offsets, "out.offsets", torch.int32, (max_buckets(n, n_scans, params) + 1,))
+        _need(out.scan_bucket_start, "out.scan_bucket_start", torch.int32, (n_scans + 1,))
+        _need(out.placed_per_round, "out.placed_per_round", torch.int32, (8,), optional=True)
     if workspace is None:
         workspace = torch.empty(workspace_bytes(n, n_scans, params), dtype=torch.uint8, device=dev)
+    _need(workspace, "workspace", torch.uint8, (None,))
     rc = lib().f3d_psh_bucketize(_ptr(coords), _ptr(batch_offsets), n, n_scans, ctypes.byref(params), _ptr(out.perm),
                                  _ptr(out.inv_perm), _ptr(out.offsets), _ptr(out.scan_bucket_start),
                                  _ptr(out.placed_per_round), _ptr(workspace), workspace.numel(), _stream())
@@ -205,12 +238,16 @@ def bucket_swin_attn(q, k, v, buckets: Buckets, heads: int, head_dim: int, mode:
     unpermute folded into the kernel's store). lse: optional float32 [n, heads] tensor that receives the rows'
     log-sum-exp (bucket-major), for the backward pass."""
     import torch
-    assert q.dtype in (torch.bfloat16, torch.float16)
-    for t in (q, k, v):
-        assert t.is_cuda and t.dtype == q.dtype and t.is_contiguous() and t.shape == (buckets.n, heads * head_dim)
+    if q.dtype not in (torch.bfloat16, torch.float16):
+        raise TypeError("q, k, v must be bfloat16 or float16")
+    shape = (buckets.n, heads * head_dim)
+    for name, t in (("q", q), ("k", k), ("v", v)):
+        _need(t, name, q.dtype, shape)
     if out is None:
         out = torch.empty_like(q)
-    assert out.dtype == q.dtype
+    _need(out, "out", q.dtype, shape)
+    _need(lse, "lse", torch.float32, (buckets.n, heads), optional=True)
+    _check_buckets(buckets, use_perm or original_order)
     entry = lib().f3d_bucket_swin_attn if q.dtype == torch.bfloat16 else lib().f3d_bucket_swin_attn_f16
     rc = entry(_ptr(q), _ptr(k), _ptr(v), _ptr(buckets.perm) if use_perm else None,
                                     _ptr(buckets.offsets), _ptr(buckets.scan_bucket_start), buckets.n, buckets.n_scans,
@@ -229,9 +266,10 @@ def bucket_swin_attn_bwd(q, k, v, out, dout, lse, buckets: Buckets, heads: int, 
     call. Returns (dq, dk, dv), bfloat16 [n, C], bucket-major rows or, with original_order, input order."""
     import torch
     n = buckets.n
-    for t in (q, k, v, out, dout):
-        assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.shape == (n, heads * head_dim)
-    assert lse.is_cuda and lse.dtype == torch.float32 and lse.is_contiguous() and lse.shape == (n, heads)
+    for name, t in (("q", q), ("k", k), ("v", v), ("out", out), ("dout", dout)):
+        _need(t, name, torch.bfloat16, (n, heads * head_dim))
+    _need(lse, "lse", torch.float32, (n, heads))
+    _check_buckets(buckets, use_perm or original_order)
     dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
     if workspace is None:
         nb = ctypes.c_size_t(0)
@@ -255,8 +293,16 @@ def ln_linear(x, w, bias=None, gamma=None, beta=None, eps: float = 1e-5, row_in=
     import torch
     n, c_in = int(x.shape[0]), int(x.shape[1])
     c_out = int(w.shape[0])
-    assert x.is_cuda and x.dtype == torch.bfloat16 and x.is_contiguous()
-    assert w.dtype == torch.bfloat16 and w.is_contiguous() and w.shape[1] == c_in
+    _need(x, "x", torch.bfloat16, (n, c_in))
+    _need(w, "w", torch.bfloat16, (c_out, c_in))
+    if n_outs < 1 or c_out % n_outs:
+        raise ValueError("c_out must be a multiple of n_outs")
+    _need(gamma, "gamma", torch.float32, (c_in,), optional=True)
+    _need(beta, "beta", torch.float32, (c_in,), optional=True)
+    _need(bias, "bias", torch.float32, (c_out,), optional=True)
+    _need(residual, "residual", torch.bfloat16, (n, c_out), optional=True)
+    _need(row_in, "row_in", torch.int32, (n,), optional=True)
+    _need(row_out, "row_out", torch.int32, (n,), optional=True)
     outs = tuple(torch.empty(n, c_out // n_outs, dtype=torch.bfloat16, device=x.device) for _ in range(n_outs))
     arr = (ctypes.c_void_p * n_outs)(*[t.data_ptr() for t in outs])
     rc = lib().f3d_ln_linear(_ptr(x), _ptr(row_in), _ptr(gamma), _ptr(beta), eps, _ptr(w), _ptr(bias), _ptr(residual), n, c_in,
@@ -289,14 +335,23 @@ def inbucket_pool(coords, perm, feat, batch_offsets, tile: int, rho: int, voxel_
     feat bfloat16 [n,C] bucket-major; batch_offsets int32 [n_scans+1] or None."""
     import torch
     n, C = int(feat.shape[0]), int(feat.shape[1])
-    assert coords.is_cuda and coords.dtype == torch.float32 and coords.is_contiguous() and coords.shape == (n, 3)
-    assert feat.is_cuda and feat.dtype == torch.bfloat16 and feat.is_contiguous()
+    _need(coords, "coords", torch.float32, (n, 3))
+    _need(feat, "feat", torch.bfloat16, (n, C))
+    _need(perm, "perm", torch.int32, (n,), optional=True)
+    _need(batch_offsets, "batch_offsets", torch.int32, (None,), optional=True)
     n_scans = 1 if batch_offsets is None else int(batch_offsets.shape[0]) - 1
     dev = feat.device
     if out is None:
         mr = pool_max_rows(n, n_scans, tile, rho)
         out = Pooled(torch.empty(mr, C, dtype=torch.bfloat16, device=dev), torch.empty(mr, 3, dtype=torch.float32, device=dev),
                      torch.empty(n, dtype=torch.int32, device=dev), torch.empty(n_scans + 1, dtype=torch.int32, device=dev), mr)
+    else:
+        mr = pool_max_rows(n, n_scans, tile, rho)
+        _need(out.feat, "out.feat", torch.bfloat16, (mr, C))
+        _need(out.coords, "out.coords", torch.float32, (mr, 3))
+        _need(out.sub_of, "out.sub_of", torch.int32, (n,))
+        _need(out.pooled_offsets, "out.pooled_offsets", torch.int32, (n_scans + 1,))
+    _need(workspace, "workspace", torch.uint8, (None,), optional=True)
     if workspace is None:
         nb = ctypes.c_size_t(0)
         rc = lib().f3d_pool_workspace_bytes(n, n_scans, tile, ctypes.byref(nb))
@@ -315,9 +370,11 @@ def inbucket_pool(coords, perm, feat, batch_offsets, tile: int, rho: int, voxel_
 def unpermute(src, perm, out=None):
     """f3d_unpermute: out[perm[p]] = src[p] for a contiguous 2-D tensor."""
     import torch
-    assert src.is_cuda and src.is_contiguous() and src.dim() == 2
+    _need(src, "src", src.dtype, (None, None))
+    _need(perm, "perm", torch.int32, (int(src.shape[0]),))
     if out is None:
         out = torch.empty_like(src)
+    _need(out, "out", src.dtype, tuple(src.shape))
     rc = lib().f3d_unpermute(_ptr(src), _ptr(perm), int(src.shape[0]), int(src.shape[1] * src.element_size()), _ptr(out),
                              _stream())
     if rc != F3D_OK:

@@ -182,3 +182,23 @@ def test_product_package_never_touches_the_oracle():
             if fn.endswith((".py", ".hip", ".h")):
                 text = open(os.path.join(dirpath, fn)).read()
                 assert "import oracle" not in text and "from oracle" not in text and "orc_" not in text, fn
+
+
+def test_binding_refuses_tensors_the_library_could_not_address():
+    """The binding hands raw addresses to the C ABI, so it checks device, layout, dtype and shape first (no GPU needed:
+    the checks run before any library call)."""
+    import torch
+    p = f3d.make_params(0.05, 256)
+    with pytest.raises(ValueError, match="coords"):
+        f3d.psh_bucketize(torch.zeros(10, 3), None, p)                       # host memory
+    bk = f3d.Buckets(None, None, None, None, None, 10, 1, 256, 4, 1)
+    with pytest.raises(TypeError):
+        f3d.bucket_swin_attn(*(torch.zeros(10, 32) for _ in range(3)), bk, 2, 16)   # float32 features
+    with pytest.raises(ValueError, match="q must be a contiguous CUDA tensor"):
+        f3d.bucket_swin_attn(*(torch.zeros(10, 32, dtype=torch.bfloat16) for _ in range(3)), bk, 2, 16)
+    with pytest.raises(ValueError, match="x must be"):
+        f3d.ln_linear(torch.zeros(4, 64, dtype=torch.bfloat16), torch.zeros(64, 64, dtype=torch.bfloat16))
+    with pytest.raises(ValueError, match="coords"):
+        f3d.inbucket_pool(torch.zeros(4, 3), None, torch.zeros(4, 8, dtype=torch.bfloat16), None, 64, 2, 0.1)
+    with pytest.raises(ValueError, match="src"):
+        f3d.unpermute(torch.zeros(4, 8), torch.zeros(4, dtype=torch.int32))

@@ -999,3 +999,30 @@ def test_calls_on_two_streams_do_not_share_state():
         for bk, out in results[j]:
             assert torch.equal(bk.perm, alone.perm) and torch.equal(bk.offsets, alone.offsets)
             assert torch.equal(out.view(torch.int16), out_alone.view(torch.int16))
+
+
+def test_binding_refuses_wrong_shapes_and_types_on_the_device():
+    """Optional arguments reach the library as bare addresses: a gamma of the wrong length, a float64 bias, a short
+    log-sum-exp buffer or a permutation of another size must be refused before anything is launched."""
+    w = wl.make_workload("tiny")
+    bk = run_bucketize(w.coords, w.batch_offsets, w.voxel_size, w.bucket_cap)
+    q, k, v = (dev(x, torch.bfloat16) for x in w.qkv())
+    n, C = q.shape
+    with pytest.raises(ValueError, match="lse"):
+        f3d.bucket_swin_attn(q, k, v, bk, w.heads, w.head_dim, lse=torch.empty(n, device=DEV))
+    with pytest.raises(ValueError, match="out"):
+        f3d.bucket_swin_attn(q, k, v, bk, w.heads, w.head_dim, out=torch.empty(n - 1, C, dtype=torch.bfloat16, device=DEV))
+    with pytest.raises(ValueError, match="k must have shape"):
+        f3d.bucket_swin_attn(q, k[:, :C // 2].contiguous(), v, bk, w.heads, w.head_dim)
+    wq = torch.zeros(3 * C, C, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(ValueError, match="gamma"):
+        f3d.ln_linear(q, wq, None, torch.ones(C + 1, device=DEV), torch.zeros(C + 1, device=DEV), n_outs=3)
+    with pytest.raises(TypeError, match="bias"):
+        f3d.ln_linear(q, wq, torch.zeros(3 * C, dtype=torch.float64, device=DEV), n_outs=3)
+    with pytest.raises(ValueError, match="row_in"):
+        f3d.ln_linear(q, wq, row_in=bk.perm[:-1].contiguous(), n_outs=3)
+    with pytest.raises(ValueError, match="perm"):
+        f3d.unpermute(q, bk.perm[:-1].contiguous())
+    with pytest.raises(ValueError, match="perm"):
+        f3d.inbucket_pool(dev(w.coords), bk.perm[:-1].contiguous(), q, None, 128, 2, 0.1)
+    torch.cuda.synchronize()
