@@ -51,12 +51,14 @@ extern "C" {
 #define F3D_SHIFT 1
 #define F3D_STRIDE 2
 
-/* How the bucketing steps are put on the GPU. The result does not depend on it. AUTO picks STEPS when the
- * per-scan count matrix is small (the paper's operating range), else GENERAL. Asking for STEPS on an input
- * that does not qualify is F3D_ERR_UNSUPPORTED. */
+/* How the bucketing steps are put on the GPU. The result does not depend on it. AUTO picks SCANS for a batch of
+ * at least 48 scans none of which holds more than 1/24 of the points (by max_scan_points) and at most 1024
+ * buckets each, else STEPS when the per-scan count matrix is small (the paper's operating range), else GENERAL.
+ * Asking for STEPS or SCANS on an input that does not qualify is F3D_ERR_UNSUPPORTED. */
 #define F3D_SCHEDULE_AUTO 0
 #define F3D_SCHEDULE_GENERAL 1 /* two launches per step, any size                                      */
 #define F3D_SCHEDULE_STEPS 2   /* one launch per step                                                  */
+#define F3D_SCHEDULE_SCANS 3   /* one launch, one workgroup per scan: batches of many scans            */
 
 /* Variants of the rebalancing (Section 4.1 "Bucket rebalancing": Algorithm 2 leaves the arrival order of the
  * contenders of a bucket to the hardware race, and the probe offsets open, calling them randomly perturbed).

@@ -18,7 +18,7 @@ F3D_OK = 0
 ERR_INVALID_ARG, ERR_BAD_ALIGNMENT, ERR_WORKSPACE_TOO_SMALL, ERR_UNSUPPORTED, ERR_HIP = -1, -2, -3, -4, -5
 HASHES = {"xor_mod": 0, "xor_div": 1, "zorder_mod": 2, "zorder_div": 3}
 MODES = {"plain": 0, "shift": 1, "stride": 2}
-SCHEDULES = {"auto": 0, "general": 1, "steps": 2}
+SCHEDULES = {"auto": 0, "general": 1, "steps": 2, "scans": 3}
 ORDERS = {"index": 0, "canonical": 1}
 PROBE_MODES = {"axes": 0, "table": 1, "seeded": 2}
 

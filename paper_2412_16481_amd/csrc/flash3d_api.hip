@@ -35,6 +35,9 @@ struct Plan {
     size_t o_status, o_p0, o_c0, o_mm, o_cnt, o_cnt2, o_hist, o_key, o_left, o_leftpre, o_freepre, o_inv, o_rc, o_cfg, o_done, o_ci;
     // canonical order only
     size_t o_obox, o_owords, o_oidx0, o_oidx1, o_ohist, o_ocoords, o_operm;
+    // one workgroup per scan only: the two lists of points still unplaced (index, packed voxel)
+    bool scans;
+    size_t o_lidx0, o_lidx1, o_lvox0, o_lvox1;
 };
 
 int check_params(int64_t n, int32_t n_scans, const f3d_params* p)
@@ -46,7 +49,7 @@ int check_params(int64_t n, int32_t n_scans, const f3d_params* p)
     if (p->hash < 0 || p->hash > 3) return F3D_ERR_INVALID_ARG;
     if (p->n_probes < 0 || p->n_probes > F3D_MAX_PROBES) return F3D_ERR_INVALID_ARG;
     if (p->div < 0 || p->probe_step < 0 || p->max_scan_points < 0) return F3D_ERR_INVALID_ARG;
-    if (p->schedule < F3D_SCHEDULE_AUTO || p->schedule > F3D_SCHEDULE_STEPS) return F3D_ERR_INVALID_ARG;
+    if (p->schedule < F3D_SCHEDULE_AUTO || p->schedule > F3D_SCHEDULE_SCANS) return F3D_ERR_INVALID_ARG;
     if (p->order < F3D_ORDER_INDEX || p->order > F3D_ORDER_CANONICAL) return F3D_ERR_INVALID_ARG;
     if (p->probe_mode < F3D_PROBE_AXES || p->probe_mode > F3D_PROBE_SEEDED) return F3D_ERR_INVALID_ARG;
     if (p->bucket_cap % (16 * p->scope_buckets) != 0) return F3D_ERR_INVALID_ARG;
@@ -58,6 +61,14 @@ int check_params(int64_t n, int32_t n_scans, const f3d_params* p)
     if (msp > n) msp = n;
     if ((msp + S - 1) / S > F3D_MAX_SCAN_BUCKETS) return F3D_ERR_UNSUPPORTED;
     return F3D_OK;
+}
+
+// One workgroup per scan pays when the scans themselves fill the GPU and none of them is a large share of the work.
+bool wants_scans(int64_t n, int32_t n_scans, const f3d_params* p, long long max_scan_points, int kcap)
+{
+    if (!f3d::psh_scan_eligible(kcap)) return false;
+    if (p->schedule == F3D_SCHEDULE_SCANS) return true;
+    return p->schedule == F3D_SCHEDULE_AUTO && n_scans >= 48 && max_scan_points * 24 <= n;
 }
 
 void make_plan(int64_t n, int32_t n_scans, const f3d_params* p, Plan* pl)
@@ -101,6 +112,13 @@ void make_plan(int64_t n, int32_t n_scans, const f3d_params* p, Plan* pl)
         pl->o_ohist = take(f3d::order_hist_bytes(n));
         pl->o_ocoords = take((size_t)n * 12);
         pl->o_operm = take((size_t)n * 4);
+    }
+    pl->scans = wants_scans(n, n_scans, p, pl->max_scan_points, pl->kcap);
+    if (pl->scans) {
+        pl->o_lidx0 = take((size_t)n * 4);
+        pl->o_lidx1 = take((size_t)n * 4);
+        pl->o_lvox0 = take((size_t)n * 8);
+        pl->o_lvox1 = take((size_t)n * 8);
     }
     pl->bytes = at;
 }
@@ -217,6 +235,8 @@ int f3d_psh_bucketize(const float* coords, const int32_t* batch_offsets, int64_t
     (void)hipGetLastError();  // a stale error left by an earlier, unrelated runtime call is not ours
     const bool fast_ok = f3d::psh_fast_eligible(pl.max_scan_points, pl.kcap);
     int schedule = p->schedule;
+    if (schedule == F3D_SCHEDULE_SCANS && !pl.scans) return F3D_ERR_UNSUPPORTED;
+    if (pl.scans) schedule = F3D_SCHEDULE_SCANS;
     if (schedule == F3D_SCHEDULE_AUTO) schedule = fast_ok ? F3D_SCHEDULE_STEPS : F3D_SCHEDULE_GENERAL;
     if (schedule == F3D_SCHEDULE_STEPS && !fast_ok) return F3D_ERR_UNSUPPORTED;
     // canonical order: sort the points, bucket the sorted copy by index, map the result back through the sort
@@ -241,8 +261,12 @@ int f3d_psh_bucketize(const float* coords, const int32_t* batch_offsets, int64_t
         a.perm = (int32_t*)(ws + pl.o_operm);
         a.inv_perm = (int32_t*)(ws + pl.o_inv);
     }
-    hipError_t e = schedule == F3D_SCHEDULE_GENERAL ? f3d::psh_launch(a, (hipStream_t)stream)
-                                                    : f3d::psh_fast_launch(a, (hipStream_t)stream);
+    hipError_t e;
+    if (schedule == F3D_SCHEDULE_SCANS)
+        e = f3d::psh_scan_launch(a, (int32_t*)(ws + pl.o_lidx0), (int32_t*)(ws + pl.o_lidx1), (unsigned long long*)(ws + pl.o_lvox0),
+                                 (unsigned long long*)(ws + pl.o_lvox1), (hipStream_t)stream);
+    else
+        e = schedule == F3D_SCHEDULE_GENERAL ? f3d::psh_launch(a, (hipStream_t)stream) : f3d::psh_fast_launch(a, (hipStream_t)stream);
     if (e == hipSuccess && order)
         e = f3d::order_compose_launch(order, a.perm, a.inv_perm, (int)n, a.status, perm, inv_perm, (hipStream_t)stream);
     return e == hipSuccess ? F3D_OK : hip_fail(e);

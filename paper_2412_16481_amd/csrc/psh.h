@@ -51,10 +51,14 @@ struct PshArgs {
     int4* chunk_info;  // [chunks][2] {scan, chunk in scan, chunks of scan, first point}, {end point, first bucket, buckets, first chunk}; null = not wanted
     int n_chunks_ub;   // rows of chunk_info
     int32_t* done;     // [n_scans] workgroups of a scan that finished the bounding box (fast path)
+    int meta_light;    // the set-up kernel leaves the bucket offsets of the scans to the caller's kernels (batch path)
 };
 
 hipError_t psh_launch(const PshArgs& args, hipStream_t stream);       // any size
 hipError_t psh_fast_launch(const PshArgs& args, hipStream_t stream);  // small count matrix
+hipError_t psh_scan_launch(const PshArgs& args, int32_t* lidx0, int32_t* lidx1, unsigned long long* lvox0,
+                           unsigned long long* lvox1, hipStream_t stream);    // one workgroup per scan: batches of many scans
+bool psh_scan_eligible(int kcap);
 bool psh_fast_eligible(long long max_scan_points, int kcap);
 size_t psh_fast_matrix_bytes(long long n, int n_scans, int kcap);
 __global__ void k_psh_meta(PshArgs a);

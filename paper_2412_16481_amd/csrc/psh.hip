@@ -72,7 +72,7 @@ __global__ __launch_bounds__(1024) void k_psh_meta(PshArgs a)
     __syncthreads();
     if (isbad) return;
     // first row of every bucket: buckets are full except the last of a scan
-    for (int b = 0; b < a.n_scans; ++b) {
+    for (int b = 0; b < (a.meta_light ? 0 : a.n_scans); ++b) {
         const int p0 = a.scan_p0[b], nb = a.scan_p0[b + 1] - p0;
         const int kb0 = a.sbs[b], K = a.sbs[b + 1] - kb0;
         for (int j = tid; j < K; j += 1024) {

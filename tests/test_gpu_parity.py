@@ -64,7 +64,7 @@ def test_bucketize_matches_oracle_on_workloads(name, hash):
     check_bucketize(w.coords, w.batch_offsets, w.voxel_size, w.bucket_cap, w.scope_buckets, hash)
 
 
-@pytest.mark.parametrize("schedule", ["general", "steps"])
+@pytest.mark.parametrize("schedule", ["general", "steps", "scans"])
 @pytest.mark.parametrize("name,hash", [("tiny", "xor_mod"), ("indoor", "zorder_div"), ("indoor", "xor_div"), ("lidar4", "zorder_mod")])
 def test_bucketize_every_schedule_gives_the_oracle_result(name, hash, schedule):
     # the two ways of putting the steps on the GPU (two launches per step, one per step) are the same function
@@ -74,7 +74,7 @@ def test_bucketize_every_schedule_gives_the_oracle_result(name, hash, schedule):
                     max_scan_points=largest)
 
 
-@pytest.mark.parametrize("schedule", ["general", "steps"])
+@pytest.mark.parametrize("schedule", ["general", "steps", "scans"])
 def test_bucketize_schedules_on_ragged_scans(schedule):
     rng = np.random.default_rng(27)
     sizes = [1, 2047, 2048, 2049, 0, 5000, 77, 0, 12000]
@@ -82,6 +82,44 @@ def test_bucketize_schedules_on_ragged_scans(schedule):
     c = np.concatenate([wl.uniform_cube(rng, s, 1.0 + i) + 10.0 * i for i, s in enumerate(sizes)]).astype(np.float32)
     for n_probes in (0, 3, 6):
         check_bucketize(c, bo, 0.05, 256, 4, "zorder_div", n_probes, schedule=schedule)
+
+
+@pytest.mark.parametrize("n", [1, 5, 64, 65, 2047, 2048, 2049, 4097, 20000])
+def test_bucketize_one_workgroup_per_scan_small_and_ragged_sizes(n):
+    rng = np.random.default_rng(300 + n)
+    c = clustered_cloud(rng, n)
+    for hash in HASHES:
+        check_bucketize(c, None, 0.05, 128, 4, hash, schedule="scans")
+    check_bucketize(c, None, 0.05, 1 << 17, 4, "zorder_div", n_probes=0, schedule="scans")   # one bucket, no probes
+    check_bucketize(c, None, 0.05, 256, 2, "xor_div", n_probes=3, schedule="scans", order="canonical")
+
+
+def test_bucketize_batches_of_many_scans_take_the_scan_path_by_themselves():
+    """100 uneven scans (some empty), none above 1/24 of the points: the automatic choice is one workgroup per scan
+    (its workspace holds the two lists of unplaced points); the result is the oracle's whatever the schedule."""
+    rng = np.random.default_rng(310)
+    sizes = rng.integers(0, 3000, 100)
+    sizes[[3, 50, 99]] = 0
+    sizes[7] = 1
+    bo = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    n = int(bo[-1])
+    c = np.concatenate([clustered_cloud(rng, int(sz), 2.0 * i) for i, sz in enumerate(sizes)]).astype(np.float32).reshape(n, 3)
+    largest = int(sizes.max())
+    p_auto = f3d.make_params(0.05, 256, 4, "zorder_div", max_scan_points=largest)
+    p_steps = f3d.make_params(0.05, 256, 4, "zorder_div", max_scan_points=largest, schedule="steps")
+    assert f3d.workspace_bytes(n, 100, p_auto) >= f3d.workspace_bytes(n, 100, p_steps) + 24 * n
+    for hash in ("zorder_div", "xor_mod"):
+        for schedule in ("auto", "scans", "steps"):
+            check_bucketize(c, bo, 0.05, 256, 4, hash, max_scan_points=largest, schedule=schedule)
+    check_bucketize(c, bo, 0.05, 256, 4, "zorder_mod", max_scan_points=largest, probe_mode="seeded", probe_seed=5)
+    check_bucketize(c, bo, 0.05, 256, 4, "xor_div", max_scan_points=largest, order="canonical")
+
+
+def test_bucketize_one_workgroup_per_scan_is_refused_above_1024_buckets_per_scan():
+    p = f3d.make_params(0.05, 64, 4, "zorder_div", schedule="scans")      # S = 16: 20000 points are 1250 buckets
+    with pytest.raises(f3d.Flash3DError) as e:
+        f3d.psh_bucketize(dev(np.zeros((20000, 3), np.float32)), None, p)
+    assert e.value.code == f3d.ERR_UNSUPPORTED
 
 
 def test_bucketize_one_launch_per_step_is_refused_for_a_large_count_matrix():
@@ -185,7 +223,7 @@ def clustered_cloud(rng, n, offset=0.0):
     return (centres[rng.integers(0, 12, n)] + rng.normal(0, 0.08, (n, 3)) + offset).astype(np.float32)
 
 
-@pytest.mark.parametrize("schedule", ["general", "steps"])
+@pytest.mark.parametrize("schedule", ["general", "steps", "scans"])
 @pytest.mark.parametrize("name,hash", [("tiny", "xor_mod"), ("indoor", "zorder_div"), ("lidar4", "xor_div"), ("lidar4", "zorder_mod")])
 def test_bucketize_canonical_order_matches_oracle(name, hash, schedule):
     w = wl.make_workload(name)
@@ -247,7 +285,7 @@ def test_bucketize_canonical_order_flags_bad_offsets_without_faulting():
         assert int(bk.scan_bucket_start[-1]) == -1
 
 
-@pytest.mark.parametrize("schedule", ["general", "steps"])
+@pytest.mark.parametrize("schedule", ["general", "steps", "scans"])
 @pytest.mark.parametrize("hash", HASHES)
 def test_bucketize_probe_table_and_seeded_probes_match_oracle(hash, schedule):
     rng = np.random.default_rng(34)
@@ -936,7 +974,7 @@ def test_random_configurations_of_every_entry_point(seed):
     coords = np.concatenate([random_cloud(rng, int(bo[i + 1] - bo[i]), kind) + 3.0 * i for i in range(n_scans)]).reshape(n, 3)
     m = int(rng.choice([1, 2, 3, 4, 8, 16]))
     cap = 16 * m * int(rng.choice([1, 2, 4, 8, 16]))
-    kw = {"order": str(rng.choice(["index", "index", "canonical"])), "schedule": str(rng.choice(["auto", "general"])),
+    kw = {"order": str(rng.choice(["index", "index", "canonical"])), "schedule": str(rng.choice(["auto", "general", "scans"])),
           "probe_mode": str(rng.choice(["axes", "axes", "seeded", "table"])), "probe_seed": int(rng.integers(0, 2 ** 31)),
           "probe_table": rng.integers(-5, 6, (6, 3)).tolist(), "max_scan_points": int(np.diff(bo).max())}
     if rng.random() < 0.2:
