@@ -52,8 +52,8 @@ extern "C" {
 #define F3D_STRIDE 2
 
 /* How the bucketing steps are put on the GPU. The result does not depend on it. AUTO picks SCANS for a batch of
- * at least 48 scans none of which holds more than 1/24 of the points (by max_scan_points) and at most 1024
- * buckets each, else STEPS when the per-scan count matrix is small (the paper's operating range), else GENERAL.
+ * at least 48 scans of at most 1024 buckets each when a cost estimate from n, n_scans and max_scan_points favours
+ * it (many scans, none of them a large share of the points), else STEPS when the per-scan count matrix is small (the paper's operating range), else GENERAL.
  * Asking for STEPS or SCANS on an input that does not qualify is F3D_ERR_UNSUPPORTED. */
 #define F3D_SCHEDULE_AUTO 0
 #define F3D_SCHEDULE_GENERAL 1 /* two launches per step, any size                                      */

@@ -147,6 +147,8 @@ __device__ inline void tile_hash_cfg(int hash, int M, const int* vmax, ScanCfg& 
     if (hash == 3) D = udiv63_small(morton3(vmax[0], vmax[1], vmax[2]), K, c.invK) + 1;
     c.D = D;
     c.invD = 1.0 / (double)D;
+    c.invDf = (float)c.invD;
+    c.wide = vm >= 2048;
     c.m32 = umod52(4294967296ull, K, c.invK);
     c.step = 1;
 }

@@ -65,6 +65,8 @@ struct ScanCfg {
     int nb;                 // points
     int kb0;                // first bucket (global index)
     int lastcap;            // capacity of the scan's last bucket
+    float invDf;            // 1/D in binary32: quotient estimate of the *_DIV hashes (the result is clamped below 2^13)
+    int wide;               // some voxel coordinate of the scan needs more than 11 bits
 };
 
 __device__ __forceinline__ int voxel_of(float c, float mn, float inv)
@@ -102,13 +104,20 @@ __device__ __forceinline__ unsigned int umod_q32(unsigned long long x, int K, do
     return (unsigned int)r;
 }
 
+// the same code when every coordinate is below 2^11: its upper 30 bits are zero
+__device__ __forceinline__ uint64_t morton3_low(int x, int y, int z)
+{
+    const uint32_t lx = spread11((uint32_t)x), ly = spread11((uint32_t)y), lz = spread11((uint32_t)z);
+    return (uint64_t)lx | ((uint64_t)ly << 1) | ((uint64_t)lz << 2);
+}
+
 __device__ __forceinline__ int hash_bucket(int hash, int x, int y, int z, const ScanCfg& c)
 {
     unsigned long long code;
     if (hash == 0 || hash == 1)
         code = (unsigned long long)((uint32_t)x ^ (uint32_t)y ^ (uint32_t)z);
     else
-        code = morton3(x, y, z);
+        code = c.wide ? morton3(x, y, z) : morton3_low(x, y, z);
     if (hash == 0 || hash == 2) {
         if (c.K < 2) return 0;
         // code = hi*2^32 + lo  =>  code mod K = ((hi mod K) * (2^32 mod K) + lo) mod K; K < 2^13 keeps the
@@ -117,11 +126,16 @@ __device__ __forceinline__ int hash_bucket(int hash, int x, int y, int z, const 
         const unsigned long long t = (unsigned long long)umod_q32(hi, c.K, c.invK) * c.m32 + lo;
         return (int)umod_q32(t, c.K, c.invK);
     }
-    // code / D clamped to K-1. The binary64 estimate is within one of the true quotient whenever it is below 2^31;
-    // above that the true quotient is certainly >= K.
-    const double qd = u64_to_double(code) * c.invD;
-    if (qd >= 2147483648.0) return c.K - 1;
-    long long q = (long long)__double2uint_rz(qd);
+    // code / D clamped to K-1, K < 2^13 + 1. A binary32 estimate (code, 1/D and their product each rounded once more
+    // than exactly: relative error below 2^-22) is within 0.002 of the true quotient wherever it is below K + 1, so its
+    // integer part is within one of the true one and one correction step with the exact remainder settles it; at K + 1
+    // and above the true quotient is certainly >= K. With K >= 2 the divisor is at most 2^62 + 1 and the product below
+    // stays inside 64 bits.
+    if (c.K < 2) return 0;
+    const float cf = __fmaf_rn(__uint2float_rn((unsigned int)(code >> 32)), 4294967296.0f, __uint2float_rn((unsigned int)code));
+    const float qf = cf * c.invDf;
+    if (qf >= (float)(c.K + 1)) return c.K - 1;
+    long long q = (long long)__float2uint_rz(qf);
     const long long r = (long long)(code - (unsigned long long)(unsigned int)q * c.D);
     if (r < 0) --q;
     else if ((unsigned long long)r >= c.D) ++q;
@@ -221,6 +235,8 @@ __device__ inline void compute_cfg(const PshArgs& a, int b, const uint32_t* box,
     if (a.div > 0) D = (unsigned long long)a.div;
     c.D = D;
     c.invD = 1.0 / (double)D;
+    c.invDf = (float)c.invD;
+    c.wide = vm >= 2048;
     c.m32 = umod52(4294967296ull, K, c.invK);
     long long step = 1;
     if (a.hash == 1) step = (long long)(D > (unsigned long long)F3D_VOXEL_MAX ? (unsigned long long)F3D_VOXEL_MAX : D);
@@ -262,10 +278,14 @@ __device__ inline int block_excl_scan(int v, int* total, int* lds /*[17]*/)
 // lanes of the wave whose key equals this lane's key (ballots over the key bits); 0 for inactive lanes
 __device__ __forceinline__ unsigned long long match_key(int key, bool active, int keybits)
 {
-    unsigned long long m = __ballot(active);
+    // Inactive lanes take key 0 and are never in the starting mask, so a ballot needs no "and active": the compare
+    // writes the lane mask directly (the compiler builtin takes the predicate as it is; __ballot() goes through an
+    // integer and back).
+    unsigned long long m = __builtin_amdgcn_ballot_w64(active);
+    const int k = active ? key : 0;
     for (int bit = 0; bit < keybits; ++bit) {
-        const bool one = (key >> bit) & 1;
-        const unsigned long long bal = __ballot(active && one);
+        const bool one = (k >> bit) & 1;
+        const unsigned long long bal = __builtin_amdgcn_ballot_w64(one);
         m &= one ? bal : ~bal;
     }
     return active ? m : 0ull;

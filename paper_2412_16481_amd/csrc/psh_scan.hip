@@ -31,7 +31,10 @@ __device__ __forceinline__ unsigned long long pack_voxel(int x, int y, int z)
     return (unsigned long long)(uint32_t)x | ((unsigned long long)(uint32_t)y << 21) | ((unsigned long long)(uint32_t)z << 42);
 }
 
-// dynamic LDS, in 32-bit words: fill[K] run[2][K] wh[SNW][kw] wbase[SNW][kw] with kw = (K + 1) / 2
+// dynamic LDS, in 32-bit words: fill[K] run[2][K] wh[SNW][kw] wbase[SNW][kw] with kw = (K + 1) / 2.
+// The hash function is a template parameter: the kernel holds many scan-wide values in scalar registers, and the
+// branches between four hash functions cost enough of them to spill.
+template <int HASH>
 __global__ __launch_bounds__(STH) void k_pshs_scan(PshArgs a, int32_t* __restrict__ lidx0, int32_t* __restrict__ lidx1,
                                                    unsigned long long* __restrict__ lvox0, unsigned long long* __restrict__ lvox1)
 {
@@ -112,10 +115,45 @@ __global__ __launch_bounds__(STH) void k_pshs_scan(PshArgs a, int32_t* __restric
         unsigned long long pend_vox[SPPT];
         bool pend[SPPT] = {false, false};
         const int n_it = (n_in + SIT - 1) / SIT;
+        // The entries of an iteration are requested one iteration ahead (three words each: the coordinates in step 0,
+        // index and packed voxel afterwards), so that an iteration does not start by waiting for memory.
+        uint32_t nw0[SPPT], nw1[SPPT], nw2[SPPT];
+#pragma unroll
+        for (int s = 0; s < SPPT; ++s) {
+            const int j = wave * (SIT / SNW) + s * 64 + lane;
+            nw0[s] = nw1[s] = nw2[s] = 0u;
+            if (j < n_in) {
+                if (r == 0) {
+                    const uint32_t* c = reinterpret_cast<const uint32_t*>(a.coords + (size_t)(p0 + j) * 3);
+                    nw0[s] = c[0]; nw1[s] = c[1]; nw2[s] = c[2];
+                } else {
+                    const unsigned long long v = in_vox[p0 + j];
+                    nw0[s] = (uint32_t)in_idx[p0 + j]; nw1[s] = (uint32_t)v; nw2[s] = (uint32_t)(v >> 32);
+                }
+            }
+        }
         for (int it = 0; it < n_it; ++it) {
             int idx[SPPT], hh[SPPT], wl[SPPT];
             unsigned long long vox[SPPT];
             bool act[SPPT];
+            uint32_t w0[SPPT], w1[SPPT], w2[SPPT];
+#pragma unroll
+            for (int s = 0; s < SPPT; ++s) { w0[s] = nw0[s]; w1[s] = nw1[s]; w2[s] = nw2[s]; }
+            if (it + 1 < n_it) {
+#pragma unroll
+                for (int s = 0; s < SPPT; ++s) {
+                    const int j = (it + 1) * SIT + wave * (SIT / SNW) + s * 64 + lane;
+                    if (j < n_in) {
+                        if (r == 0) {
+                            const uint32_t* c = reinterpret_cast<const uint32_t*>(a.coords + (size_t)(p0 + j) * 3);
+                            nw0[s] = c[0]; nw1[s] = c[1]; nw2[s] = c[2];
+                        } else {
+                            const unsigned long long v = in_vox[p0 + j];
+                            nw0[s] = (uint32_t)in_idx[p0 + j]; nw1[s] = (uint32_t)v; nw2[s] = (uint32_t)(v >> 32);
+                        }
+                    }
+                }
+            }
 #pragma unroll
             for (int s = 0; s < SPPT; ++s) {
                 const int j = it * SIT + wave * (SIT / SNW) + s * 64 + lane;
@@ -124,13 +162,13 @@ __global__ __launch_bounds__(STH) void k_pshs_scan(PshArgs a, int32_t* __restric
                 vox[s] = 0ull;
                 if (act[s]) {
                     if (r == 0) {
-                        const float* c = a.coords + (size_t)(p0 + j) * 3;
                         idx[s] = j;
-                        vox[s] = pack_voxel(voxel_of(c[0], cfg.mn[0], a.inv_voxel), voxel_of(c[1], cfg.mn[1], a.inv_voxel),
-                                            voxel_of(c[2], cfg.mn[2], a.inv_voxel));
+                        vox[s] = pack_voxel(voxel_of(__uint_as_float(w0[s]), cfg.mn[0], a.inv_voxel),
+                                            voxel_of(__uint_as_float(w1[s]), cfg.mn[1], a.inv_voxel),
+                                            voxel_of(__uint_as_float(w2[s]), cfg.mn[2], a.inv_voxel));
                     } else {
-                        idx[s] = in_idx[p0 + j];
-                        vox[s] = in_vox[p0 + j];
+                        idx[s] = (int)w0[s];
+                        vox[s] = (unsigned long long)w1[s] | ((unsigned long long)w2[s] << 32);
                     }
                 }
             }
@@ -140,7 +178,7 @@ __global__ __launch_bounds__(STH) void k_pshs_scan(PshArgs a, int32_t* __restric
                 if (act[s]) {
                     int x = (int)(vox[s] & 0x1FFFFFull), y = (int)((vox[s] >> 21) & 0x1FFFFFull), z = (int)(vox[s] >> 42);
                     if (r > 0) probe_voxel(a, r, cfg, x, y, z);
-                    h = hash_bucket(a.hash, x, y, z, cfg);
+                    h = hash_bucket(HASH, x, y, z, cfg);
                 }
                 hh[s] = h;
             }
@@ -325,11 +363,18 @@ hipError_t psh_scan_launch(const PshArgs& args, int32_t* lidx0, int32_t* lidx1, 
     if (a.n == 0) return hipGetLastError();
     const size_t kw = (size_t)(a.kcap + 1) / 2;
     const size_t lds = ((size_t)3 * a.kcap + 2 * SNW * kw) * 4;
+    const void* fn[4] = {(const void*)k_pshs_scan<0>, (const void*)k_pshs_scan<1>, (const void*)k_pshs_scan<2>,
+                         (const void*)k_pshs_scan<3>};
     if (lds > 60000) {
-        const hipError_t e = hipFuncSetAttribute((const void*)k_pshs_scan, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        const hipError_t e = hipFuncSetAttribute(fn[a.hash & 3], hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    k_pshs_scan<<<a.n_scans, STH, lds, stream>>>(a, lidx0, lidx1, lvox0, lvox1);
+    switch (a.hash) {
+        case 0: k_pshs_scan<0><<<a.n_scans, STH, lds, stream>>>(a, lidx0, lidx1, lvox0, lvox1); break;
+        case 1: k_pshs_scan<1><<<a.n_scans, STH, lds, stream>>>(a, lidx0, lidx1, lvox0, lvox1); break;
+        case 2: k_pshs_scan<2><<<a.n_scans, STH, lds, stream>>>(a, lidx0, lidx1, lvox0, lvox1); break;
+        default: k_pshs_scan<3><<<a.n_scans, STH, lds, stream>>>(a, lidx0, lidx1, lvox0, lvox1); break;
+    }
     return hipGetLastError();
 }
 
