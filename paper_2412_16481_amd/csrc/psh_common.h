@@ -159,11 +159,14 @@ __device__ __forceinline__ uint32_t mix32(uint32_t x)
 // axis drawn from (seed, r, voxel), so that the points of a voxel move together whatever their indices are.
 __device__ __forceinline__ void probe_voxel(const PshArgs& a, int r, const ScanCfg& c, int& x, int& y, int& z)
 {
-    long long dx = 0, dy = 0, dz = 0;
+    // Voxel coordinates are below 2^21, so an offset beyond +-2^22 lands outside the box exactly as +-2^22 does: with
+    // the offsets limited to that, the sums fit 32 bits.
+    constexpr int LIM = 1 << 22;
+    int dx = 0, dy = 0, dz = 0;
     if (a.probe_mode == 1) {
-        dx = a.probe_table[3 * (r - 1)];
-        dy = a.probe_table[3 * (r - 1) + 1];
-        dz = a.probe_table[3 * (r - 1) + 2];
+        dx = min(max(a.probe_table[3 * (r - 1)], -LIM), LIM);
+        dy = min(max(a.probe_table[3 * (r - 1) + 1], -LIM), LIM);
+        dz = min(max(a.probe_table[3 * (r - 1) + 2], -LIM), LIM);
     } else {
         int dir = r - 1;
         if (a.probe_mode == 2) {
@@ -173,15 +176,16 @@ __device__ __forceinline__ void probe_voxel(const PshArgs& a, int r, const ScanC
             h = mix32(h ^ (uint32_t)z);
             dir = (int)(((unsigned long long)h * 6ull) >> 32);
         }
-        const long long d = (dir & 1) ? -(long long)c.step : (long long)c.step;
+        const int st = min(c.step, LIM);              // a caller's step may be any positive int
+        const int d = (dir & 1) ? -st : st;
         const int ax = dir >> 1;
         dx = ax == 0 ? d : 0;
         dy = ax == 1 ? d : 0;
         dz = ax == 2 ? d : 0;
     }
-    x = (int)min(max((long long)x + dx, 0ll), (long long)c.vmax[0]);
-    y = (int)min(max((long long)y + dy, 0ll), (long long)c.vmax[1]);
-    z = (int)min(max((long long)z + dz, 0ll), (long long)c.vmax[2]);
+    x = min(max(x + dx, 0), c.vmax[0]);
+    y = min(max(y + dy, 0), c.vmax[1]);
+    z = min(max(z + dz, 0), c.vmax[2]);
 }
 
 // largest b in [0, n_scans) with start[b] <= x, given start[0] <= x < start[n_scans]

@@ -122,6 +122,19 @@ def test_bucketize_one_workgroup_per_scan_is_refused_above_1024_buckets_per_scan
     assert e.value.code == f3d.ERR_UNSUPPORTED
 
 
+@pytest.mark.parametrize("schedule", ["general", "steps", "scans"])
+def test_bucketize_probe_offsets_at_the_limits_of_int32(schedule):
+    """A probe step or a table offset of any size is legal: the moved voxel is clamped to the scan's voxel box."""
+    rng = np.random.default_rng(320)
+    c = clustered_cloud(rng, 9000)
+    big = 2 ** 31 - 1
+    check_bucketize(c, None, 0.01, 256, 4, "zorder_div", probe_step=big, schedule=schedule)
+    check_bucketize(c, None, 0.01, 256, 4, "xor_mod", probe_step=1 << 22, schedule=schedule)
+    table = [[big, 0, 0], [-big - 1, 3, 0], [0, -big, big], [1 << 21, -(1 << 21), 0], [5, 5, -5], [-(1 << 22) - 1, (1 << 22) + 1, 7]]
+    check_bucketize(c, None, 0.01, 256, 4, "zorder_mod", probe_mode="table", probe_table=table, schedule=schedule)
+    check_bucketize(c, None, 1e-6, 256, 4, "xor_div", probe_mode="table", probe_table=table, schedule=schedule)   # saturated voxels
+
+
 def test_bucketize_one_launch_per_step_is_refused_for_a_large_count_matrix():
     w = wl.make_workload("lidar8")   # taken as ONE scan of 9e5 points: 447 chunks x 3573 buckets
     p = f3d.make_params(w.voxel_size, w.bucket_cap, w.scope_buckets, "zorder_div", schedule="steps")
