@@ -69,13 +69,16 @@ __global__ __launch_bounds__(1024) void k_psh_meta(PshArgs a)
         a.status[0] = isbad;
     }
     if (tid < 8) a.round_count[tid] = 0;
+    __threadfence_block();   // the scan tables just written are read below by other threads (the barrier alone orders LDS)
     __syncthreads();
     if (isbad) return;
-    // first row of every bucket: buckets are full except the last of a scan
-    for (int b = 0; b < (a.meta_light ? 0 : a.n_scans); ++b) {
+    // first row of every bucket: buckets are full except the last of a scan. A wave per scan: a batch may hold
+    // hundreds of scans, and a loop over them by the whole workgroup would be a chain of dependent loads.
+    const int lane = tid & 63, wave = tid >> 6;
+    for (int b = (a.meta_light ? a.n_scans : wave); b < a.n_scans; b += 16) {
         const int p0 = a.scan_p0[b], nb = a.scan_p0[b + 1] - p0;
         const int kb0 = a.sbs[b], K = a.sbs[b + 1] - kb0;
-        for (int j = tid; j < K; j += 1024) {
+        for (int j = lane; j < K; j += 64) {
             a.offsets[kb0 + j] = p0 + min(j * a.S, nb);
             a.cnt[kb0 + j] = 0;
         }
@@ -83,11 +86,11 @@ __global__ __launch_bounds__(1024) void k_psh_meta(PshArgs a)
     for (int j = kcarry + tid; j <= a.max_buckets; j += 1024) a.offsets[j] = a.n;
     // chunk table: everything a workgroup needs to find its points, in one load
     if (a.chunk_info) {
-        for (int b = 0; b < a.n_scans; ++b) {
+        for (int b = wave; b < a.n_scans; b += 16) {
             const int p0 = a.scan_p0[b], p1 = a.scan_p0[b + 1];
             const int kb0 = a.sbs[b], K = a.sbs[b + 1] - kb0;
             const int c0 = a.scan_c0[b], nc = a.scan_c0[b + 1] - c0;
-            for (int lc = tid; lc < nc; lc += 1024) {
+            for (int lc = lane; lc < nc; lc += 64) {
                 const int begin = p0 + lc * a.chunk;
                 a.chunk_info[2 * (c0 + lc)] = make_int4(b, lc, nc, begin);
                 a.chunk_info[2 * (c0 + lc) + 1] = make_int4(min(begin + a.chunk, p1), kb0, K, c0);
