@@ -176,9 +176,10 @@ static inline int f3d_psh_bucketize_simple(const float *coords, int64_t n, float
  *               the sum of exponentials of the row's scaled scores; what f3d_bucket_swin_attn_bwd needs
  * Arithmetic: bf16 operands, fp32 accumulation and softmax, probabilities rounded to bf16 before P*V. The scale
  * is folded into q before the product (q*scale*log2(e) carried as two bf16 terms), so a scaled score is exact to
- * about 2^-17 of |q||k| scale: far below the rounding of the probabilities for |score| up to a few hundred, and
- * visible in `lse` as an absolute error of about 4e-3 + 2^-18 |lse|. Inputs must be finite, and so must their scaled
- * scores in binary32.
+ * about 2^-17 of |q||k| scale (the product of the norms, not the score itself): far below the rounding of the
+ * probabilities while |q||k| scale stays below a few hundred, and visible in `lse` as an absolute error of about
+ * 4e-3 plus that amount. Where |q||k| scale reaches 10^4 and two top scores of a row lie within one unit of each
+ * other, single outputs move by a few 10^-2. Inputs must be finite, and so must their scaled scores in binary32.
  */
 int f3d_bucket_swin_attn(const void *q, const void *k, const void *v, const int32_t *perm, const int32_t *offsets,
                          const int32_t *scan_bucket_start, int64_t n, int32_t n_scans, int64_t max_buckets,
