@@ -383,8 +383,14 @@ __global__ __launch_bounds__(FTH) void k_pshf_recycle(PshArgs a)
         a.perm[dst] = i;
         ++placed;
     }
+    // one atomic per workgroup: hundreds of waves adding to the same counter queue up behind each other
     for (int d = 32; d >= 1; d >>= 1) placed += __shfl_xor(placed, d, 64);
-    if ((tid & 63) == 0 && placed) atomicAdd(&a.round_count[a.n_probes + 1], placed);
+    __syncthreads();              // everybody is done with s_base
+    if (tid == 0) s_base = 0;
+    __syncthreads();
+    if ((tid & 63) == 0 && placed) atomicAdd(&s_base, placed);
+    __syncthreads();
+    if (tid == 0 && s_base) atomicAdd(&a.round_count[a.n_probes + 1], s_base);
 }
 
 }  // namespace

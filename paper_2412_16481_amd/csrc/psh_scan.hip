@@ -345,7 +345,11 @@ __global__ __launch_bounds__(STH) void k_pshs_scan(PshArgs a, int32_t* __restric
         ++placed;
     }
     for (int d = 32; d >= 1; d >>= 1) placed += __shfl_xor(placed, d, 64);
-    if (lane == 0 && placed) atomicAdd(&a.round_count[a.n_probes + 1], placed);
+    if (tid == 0) s_placed = 0;   // the last step's count was read before that step's final barrier
+    __syncthreads();
+    if (lane == 0 && placed) atomicAdd(&s_placed, placed);
+    __syncthreads();
+    if (tid == 0 && s_placed) atomicAdd(&a.round_count[a.n_probes + 1], s_placed);
 }
 
 }  // namespace
