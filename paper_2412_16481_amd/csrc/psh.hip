@@ -362,8 +362,14 @@ __global__ __launch_bounds__(PSH_THREADS) void k_psh_recycle_place(PshArgs a)
         a.perm[dst] = i;
         ++mine;
     }
+    // one atomic per workgroup: per-wave atomics of thousands of workgroups on one counter queue up
+    __shared__ int s_mine;
     for (int d = 32; d >= 1; d >>= 1) mine += __shfl_xor(mine, d, 64);
-    if ((threadIdx.x & 63) == 0 && mine) atomicAdd(&a.round_count[a.n_probes + 1], mine);
+    if (threadIdx.x == 0) s_mine = 0;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0 && mine) atomicAdd(&s_mine, mine);
+    __syncthreads();
+    if (threadIdx.x == 0 && s_mine) atomicAdd(&a.round_count[a.n_probes + 1], s_mine);
 }
 
 // ------------------------------------------------------------------------------------------------
