@@ -38,6 +38,7 @@ extern "C" {
 #define F3D_ERR_WORKSPACE_TOO_SMALL (-3) /* workspace_bytes < f3d_workspace_bytes(...)                  */
 #define F3D_ERR_UNSUPPORTED (-4)         /* valid request outside the implemented limits                 */
 #define F3D_ERR_HIP (-5)                 /* a HIP runtime call failed; see f3d_last_hip_error()          */
+#define F3D_ERR_SCRATCH_LIMIT (-6)       /* f3d_psh_bucketize_static: needs > F3D_STATIC_SCRATCH_BYTES   */
 
 /* Hash functions of Section 4.1 ("Hash functions"). */
 #define F3D_HASH_XOR_MOD 0
@@ -149,6 +150,26 @@ static inline int f3d_psh_bucketize_simple(const float *coords, int64_t n, float
     return f3d_psh_bucketize(coords, NULL, n, 1, &p, perm, NULL, offsets, scan_bucket_start, NULL, workspace,
                              workspace_bytes, stream);
 }
+
+/*
+ * f3d_psh_bucketize for callers that cannot allocate device memory and have no workspace to pass: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc. Same arguments (minus the workspace), same
+ * kernels and bit-identical results; the scratch memory is a buffer of F3D_STATIC_SCRATCH_BYTES that is part of the
+ * library's device image (every GPU the library runs on holds it until the process ends). The call allocates and
+ * frees nothing.
+ *   - An input whose f3d_workspace_bytes() exceeds F3D_STATIC_SCRATCH_BYTES is refused with F3D_ERR_SCRATCH_LIMIT
+ *     before anything is launched (32 MiB serves about 1.4 M points in 8 scans with the default parameters; the
+ *     canonical order needs about five times the scratch per point).
+ *   - The buffer's address on the current device is looked up on the first call on that device (one
+ *     hipGetSymbolAddress, no allocation); make that first call outside a stream capture.
+ *   - All calls on one GPU share the one buffer, which keeps the last call's contents; the kernels initialise
+ *     everything they read, so nothing has to be cleared. Two calls that overlap in time on one GPU (different streams,
+ *     or graphs replayed concurrently) race on it: serialise them.
+ */
+#define F3D_STATIC_SCRATCH_BYTES (32u << 20)
+int f3d_psh_bucketize_static(const float *coords, const int32_t *batch_offsets, int64_t n, int32_t n_scans,
+                             const f3d_params *p, int32_t *perm, int32_t *inv_perm, int32_t *offsets,
+                             int32_t *scan_bucket_start, int32_t *placed_per_round, void *stream);
 
 /*
  * Bucket-and-Swin multi-head self-attention, forward (Section 4.2 "Zero-Overhead Bucket-Swin

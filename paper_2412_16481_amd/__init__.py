@@ -15,14 +15,15 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libflash3d.so")
 
 F3D_OK = 0
-ERR_INVALID_ARG, ERR_BAD_ALIGNMENT, ERR_WORKSPACE_TOO_SMALL, ERR_UNSUPPORTED, ERR_HIP = -1, -2, -3, -4, -5
+ERR_INVALID_ARG, ERR_BAD_ALIGNMENT, ERR_WORKSPACE_TOO_SMALL, ERR_UNSUPPORTED, ERR_HIP, ERR_SCRATCH_LIMIT = -1, -2, -3, -4, -5, -6
+STATIC_SCRATCH_BYTES = 32 << 20
 HASHES = {"xor_mod": 0, "xor_div": 1, "zorder_mod": 2, "zorder_div": 3}
 MODES = {"plain": 0, "shift": 1, "stride": 2}
 SCHEDULES = {"auto": 0, "general": 1, "steps": 2, "scans": 3}
 ORDERS = {"index": 0, "canonical": 1}
 PROBE_MODES = {"axes": 0, "table": 1, "seeded": 2}
 
-EXPORTS = ("f3d_params_default", "f3d_max_buckets", "f3d_workspace_bytes", "f3d_psh_bucketize",
+EXPORTS = ("f3d_params_default", "f3d_max_buckets", "f3d_workspace_bytes", "f3d_psh_bucketize", "f3d_psh_bucketize_static",
            "f3d_bucket_swin_attn", "f3d_bucket_swin_attn_f16", "f3d_attn_bwd_workspace_bytes", "f3d_bucket_swin_attn_bwd", "f3d_ln_linear", "f3d_pool_max_rows", "f3d_pool_workspace_bytes", "f3d_inbucket_pool",
            "f3d_unpermute", "f3d_error_string", "f3d_last_hip_error", "f3d_version")
 POOL_OPS = {"sum": 0, "mean": 1, "min": 2, "max": 3}
@@ -68,6 +69,8 @@ def lib() -> ctypes.CDLL:
         L.f3d_psh_bucketize.argtypes = [vp, vp, i64, i32, ctypes.POINTER(f3d_params), vp, vp, vp, vp, vp, vp,
                                         ctypes.c_size_t, vp]
         L.f3d_psh_bucketize.restype = ctypes.c_int
+        L.f3d_psh_bucketize_static.argtypes = [vp, vp, i64, i32, ctypes.POINTER(f3d_params), vp, vp, vp, vp, vp, vp]
+        L.f3d_psh_bucketize_static.restype = ctypes.c_int
         L.f3d_bucket_swin_attn.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, i32, i32, i32, i32, i32, i32, f32, vp, vp, vp, vp]
         L.f3d_bucket_swin_attn.restype = ctypes.c_int
         L.f3d_bucket_swin_attn_f16.argtypes = L.f3d_bucket_swin_attn.argtypes
@@ -196,8 +199,10 @@ def _check_buckets(b: "Buckets", needs_perm: bool) -> None:
     _need(b.perm, "buckets.perm", torch.int32, (b.n,), optional=not needs_perm)
 
 
-def psh_bucketize(coords, batch_offsets, params: f3d_params, workspace=None, out: Optional[Buckets] = None) -> Buckets:
-    """f3d_psh_bucketize on torch CUDA tensors. coords: float32 [n,3]; batch_offsets: int32 [n_scans+1] or None."""
+def psh_bucketize(coords, batch_offsets, params: f3d_params, workspace=None, out: Optional[Buckets] = None,
+                  static_scratch: bool = False) -> Buckets:
+    """f3d_psh_bucketize on torch CUDA tensors. coords: float32 [n,3]; batch_offsets: int32 [n_scans+1] or None.
+    static_scratch: call f3d_psh_bucketize_static instead (no workspace; with `out` given nothing is allocated)."""
     import torch
     _need(coords, "coords", torch.float32, (None, 3))
     n = int(coords.shape[0])
@@ -218,6 +223,13 @@ def psh_bucketize(coords, batch_offsets, params: f3d_params, workspace=None, out
         _need(out.offsets, "out.offsets", torch.int32, (max_buckets(n, n_scans, params) + 1,))
         _need(out.scan_bucket_start, "out.scan_bucket_start", torch.int32, (n_scans + 1,))
         _need(out.placed_per_round, "out.placed_per_round", torch.int32, (8,), optional=True)
+    if static_scratch:
+        rc = lib().f3d_psh_bucketize_static(_ptr(coords), _ptr(batch_offsets), n, n_scans, ctypes.byref(params), _ptr(out.perm),
+                                            _ptr(out.inv_perm), _ptr(out.offsets), _ptr(out.scan_bucket_start),
+                                            _ptr(out.placed_per_round), _stream())
+        if rc != F3D_OK:
+            raise Flash3DError(rc, "f3d_psh_bucketize_static")
+        return out
     if workspace is None:
         workspace = torch.empty(workspace_bytes(n, n_scans, params), dtype=torch.uint8, device=dev)
     _need(workspace, "workspace", torch.uint8, (None,))

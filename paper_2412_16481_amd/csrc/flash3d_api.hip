@@ -5,12 +5,19 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <atomic>
+
 #include "attn.h"
 #include "flash3d.h"
 #include "linear.h"
 #include "pool.h"
 #include "order.h"
 #include "psh.h"
+
+// Workspace of f3d_psh_bucketize_static: device memory that exists as soon as the code object is loaded on a GPU, so
+// that entry point never allocates. Every GPU holds its own copy at its own address. In host code the name `scratch`
+// is only a handle for hipGetSymbolAddress; the address kernels can use is asked for once per device and kept.
+static __device__ __align__(256) unsigned char scratch[F3D_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -23,6 +30,29 @@ int hip_fail(hipError_t e)
 }
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+constexpr int MAX_DEVICES = 64;
+std::atomic<char*> g_scratch_ptr[MAX_DEVICES];
+
+int static_scratch(char** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= MAX_DEVICES) return F3D_ERR_UNSUPPORTED;
+    char* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        // the current device is `dev`: the address returned is that of this GPU's copy of the array
+        void* sym = nullptr;
+        e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e);
+        if (!sym || ((uintptr_t)sym & 255)) return F3D_ERR_BAD_ALIGNMENT;
+        ptr = (char*)sym;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);   // two threads racing here store the same value
+    }
+    *out = ptr;
+    return F3D_OK;
+}
 
 struct Plan {
     int S;
@@ -184,23 +214,26 @@ int f3d_workspace_bytes(int64_t n, int32_t n_scans, const f3d_params* p, size_t*
     return F3D_OK;
 }
 
-int f3d_psh_bucketize(const float* coords, const int32_t* batch_offsets, int64_t n, int32_t n_scans, const f3d_params* p,
-                      int32_t* perm, int32_t* inv_perm, int32_t* offsets, int32_t* scan_bucket_start,
-                      int32_t* placed_per_round, void* workspace, size_t workspace_bytes, void* stream)
+// Checks that need no workspace: parameters, required pointers, alignment of the caller's arrays.
+static int check_bucketize_args(const float* coords, const int32_t* batch_offsets, int64_t n, int32_t n_scans, const f3d_params* p,
+                                int32_t* perm, int32_t* inv_perm, int32_t* offsets, int32_t* scan_bucket_start,
+                                int32_t* placed_per_round)
 {
     const int rc = check_params(n, n_scans, p);
     if (rc != F3D_OK) return rc;
-    if (!offsets || !scan_bucket_start || !workspace) return F3D_ERR_INVALID_ARG;
+    if (!offsets || !scan_bucket_start) return F3D_ERR_INVALID_ARG;
     if (n > 0 && (!coords || !perm)) return F3D_ERR_INVALID_ARG;
     if (((uintptr_t)coords | (uintptr_t)batch_offsets | (uintptr_t)perm | (uintptr_t)inv_perm | (uintptr_t)offsets |
          (uintptr_t)scan_bucket_start | (uintptr_t)placed_per_round) & 3)
         return F3D_ERR_BAD_ALIGNMENT;
-    if ((uintptr_t)workspace & 255) return F3D_ERR_BAD_ALIGNMENT;
-    Plan pl;
-    make_plan(n, n_scans, p, &pl);
-    if (workspace_bytes < pl.bytes) return F3D_ERR_WORKSPACE_TOO_SMALL;
+    return F3D_OK;
+}
 
-    char* ws = (char*)workspace;
+// Carves the workspace (device memory of at least pl.bytes, 256-byte aligned) and launches the bucketing kernels.
+static int bucketize_on(const Plan& pl, char* ws, const float* coords, const int32_t* batch_offsets, int64_t n, int32_t n_scans,
+                        const f3d_params* p, int32_t* perm, int32_t* inv_perm, int32_t* offsets, int32_t* scan_bucket_start,
+                        int32_t* placed_per_round, void* stream)
+{
     f3d::PshArgs a;
     memset(&a, 0, sizeof(a));
     a.coords = coords;
@@ -276,6 +309,39 @@ int f3d_psh_bucketize(const float* coords, const int32_t* batch_offsets, int64_t
     if (e == hipSuccess && order)
         e = f3d::order_compose_launch(order, a.perm, a.inv_perm, (int)n, a.status, perm, inv_perm, (hipStream_t)stream);
     return e == hipSuccess ? F3D_OK : hip_fail(e);
+}
+
+int f3d_psh_bucketize(const float* coords, const int32_t* batch_offsets, int64_t n, int32_t n_scans, const f3d_params* p,
+                      int32_t* perm, int32_t* inv_perm, int32_t* offsets, int32_t* scan_bucket_start,
+                      int32_t* placed_per_round, void* workspace, size_t workspace_bytes, void* stream)
+{
+    const int rc = check_bucketize_args(coords, batch_offsets, n, n_scans, p, perm, inv_perm, offsets, scan_bucket_start,
+                                        placed_per_round);
+    if (rc != F3D_OK) return rc;
+    if (!workspace) return F3D_ERR_INVALID_ARG;
+    if ((uintptr_t)workspace & 255) return F3D_ERR_BAD_ALIGNMENT;
+    Plan pl;
+    make_plan(n, n_scans, p, &pl);
+    if (workspace_bytes < pl.bytes) return F3D_ERR_WORKSPACE_TOO_SMALL;
+    return bucketize_on(pl, (char*)workspace, coords, batch_offsets, n, n_scans, p, perm, inv_perm, offsets, scan_bucket_start,
+                        placed_per_round, stream);
+}
+
+int f3d_psh_bucketize_static(const float* coords, const int32_t* batch_offsets, int64_t n, int32_t n_scans, const f3d_params* p,
+                             int32_t* perm, int32_t* inv_perm, int32_t* offsets, int32_t* scan_bucket_start,
+                             int32_t* placed_per_round, void* stream)
+{
+    const int rc = check_bucketize_args(coords, batch_offsets, n, n_scans, p, perm, inv_perm, offsets, scan_bucket_start,
+                                        placed_per_round);
+    if (rc != F3D_OK) return rc;
+    Plan pl;
+    make_plan(n, n_scans, p, &pl);
+    if (pl.bytes > (size_t)F3D_STATIC_SCRATCH_BYTES) return F3D_ERR_SCRATCH_LIMIT;
+    char* ws = nullptr;
+    const int rs = static_scratch(&ws);
+    if (rs != F3D_OK) return rs;
+    return bucketize_on(pl, ws, coords, batch_offsets, n, n_scans, p, perm, inv_perm, offsets, scan_bucket_start,
+                        placed_per_round, stream);
 }
 
 // argument checks and the launch geometry shared by the forward and backward attention calls
@@ -550,6 +616,7 @@ const char* f3d_error_string(int code)
         case F3D_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case F3D_ERR_UNSUPPORTED: return "request outside the implemented limits";
         case F3D_ERR_HIP: return "HIP runtime error";
+        case F3D_ERR_SCRATCH_LIMIT: return "input needs more scratch memory than the built-in buffer of f3d_psh_bucketize_static holds";
         default: return "unknown error code";
     }
 }
