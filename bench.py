@@ -27,7 +27,9 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 
-# HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/), keyed by workload.
+# HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command, keyed by
+# workload; the figures and the commands are in profiles/k_attn_<workload>.md. A counter run cannot be made from
+# inside the timed run, so the line carries the stored figure and says where it comes from (None = not profiled).
 MEASURED_TRAFFIC_BYTES = {"indoor": 105.8e6, "lidar8": 1874.0e6}
 
 
@@ -111,7 +113,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="indoor", help="tiny | indoor | lidar4 | wide | lidar8 (the five configurations) | scope8k (scope 8192)")
+    ap.add_argument("--workload", default="lidar8",
+                    help="tiny | indoor | lidar4 | wide | lidar8 (configurations 1-5; the default is the largest) | scope8k (scope 8192)")
     ap.add_argument("--hash", default="zorder_div")
     ap.add_argument("--cpu-rows", type=int, default=-1,
                     help="query rows the oracle computes per pass (-1 = about 20 s of host work, 0 = skip)")
@@ -160,8 +163,11 @@ def main() -> int:
     gen = torch.Generator(device=dev).manual_seed(w.seed)
     if args.dtype == "f16" and (args.pool or args.backward or args.glue):
         sys.exit("bench.py: --dtype f16 covers the forward path only")
-    elem = torch.bfloat16 if args.dtype == "bf16" else torch.float16
-    q, k, v = (torch.randn(n, C, device=dev, generator=gen, dtype=torch.float32).to(elem) for _ in range(3))
+    # the seeded N(0,1) features of the workload, the same arrays the parity tests feed to both sides (bf16 bit
+    # patterns; for --dtype f16 the same values rounded to binary16)
+    q, k, v = (torch.from_numpy(a).to(dev).view(torch.bfloat16) for a in w.qkv())
+    if args.dtype == "f16":
+        q, k, v = (t.to(torch.float16) for t in (q, k, v))
     bucket_major = args.workload == "lidar8"      # that workload keeps its layers on bucket-major features
 
     max_scan = int(np.diff(w.batch_offsets).max())
@@ -220,8 +226,12 @@ def main() -> int:
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
 
-    # the attention kernel: mean launch duration from the events recorded on the launch stream inside the timed region
-    attn_ms_per_launch = float(np.mean([ev[0].elapsed_time(ev[1]) for ev in all_events])) / len(w.modes)
+    # the attention kernel: launch duration from the events recorded on the launch stream inside the timed region
+    # (mean and standard deviation over the steps, per launch); a step's own duration is the time between the
+    # "bucketing done" events of consecutive steps
+    attn_group = np.array([ev[0].elapsed_time(ev[1]) for ev in all_events]) / len(w.modes)
+    attn_ms_per_launch = float(attn_group.mean())
+    step_ms = np.array([all_events[i][0].elapsed_time(all_events[i + 1][0]) for i in range(len(all_events) - 1)])
     # every part by itself, from a short loop after the timed region (events around each launch)
     detail = []
     for _ in range(min(args.steps, 10)):
@@ -245,6 +255,7 @@ def main() -> int:
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": ms_per_step,
+        "ms_per_step_std": float(step_ms.std(ddof=1)) if len(step_ms) > 1 else None,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -256,7 +267,10 @@ def main() -> int:
                    "unpermute": "in the last pass's store" if args.fuse_unpermute else "separate kernel"},
         "roofline": {"bound": "mfma", "kernel": "k_attn", "achieved": tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": tflops / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
-                     "flop_per_launch": attn_flop_per_launch, "ms_per_launch": attn_ms_per_launch},
+                     "traffic_source": f"profiles/k_attn_{w.name}.md (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE of this command)"
+                                       if w.name in MEASURED_TRAFFIC_BYTES else None,
+                     "flop_per_launch": attn_flop_per_launch, "ms_per_launch": attn_ms_per_launch,
+                     "ms_per_launch_std": float(attn_group.std(ddof=1)) if len(attn_group) > 1 else None},
         "parts_ms": {"bucketize": float(t_buck), "attn_per_pass": [float(x) for x in t_attn.mean(axis=0)], "unpermute": float(t_unp),
                      "from": "events around every launch, in a short loop after the timed region"},
         "bucketize": {"bound": "hbm", "achieved": buck_gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",

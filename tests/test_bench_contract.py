@@ -26,7 +26,7 @@ def test_defaults_are_one_gpu_and_a_short_run():
     import bench
     src = open(os.path.join(ROOT, "bench.py")).read()
     assert 'add_argument("--gpus", type=int, default=1)' in src
-    assert 'add_argument("--workload", default="indoor"' in src        # the workload the metric is quoted on
+    assert 'add_argument("--workload", default="lidar8"' in src        # the largest of the five configurations
     assert hasattr(bench, "cpu_baseline") and hasattr(bench, "PEAK_BF16_TFLOPS") and hasattr(bench, "PEAK_HBM_GBPS")
     assert bench.PEAK_BF16_TFLOPS == 2500.0 and bench.PEAK_HBM_GBPS == 8000.0
 
