@@ -208,6 +208,12 @@ int f3d_bucket_swin_attn(const void *q, const void *k, const void *v, const int3
                          int32_t head_dim, float softmax_scale, void *out, const int32_t *out_perm, float *lse,
                          void *stream);
 
+/* Query rows one workgroup of the attention kernel covers for a launch of this geometry: 128 (one tile of 32 query rows
+ * per wave) or 256 (two). The result does not depend on it; tests use it to know which kernel variant a case runs.
+ * Arguments as in f3d_bucket_swin_attn; a negative return value is an F3D_ERR_* code. */
+int f3d_attn_block_rows(int64_t n_scans, int64_t max_buckets, int32_t bucket_cap, int32_t scope_buckets, int32_t mode,
+                        int32_t stride, int32_t heads, int32_t head_dim);
+
 /*
  * The same attention on IEEE binary16 ("FP16") tensors, the element type the Appendix "Bucket-Swin" names for the
  * point features: q, k, v and out are binary16 [n, heads*head_dim]; every other argument, the layout and the error

@@ -24,7 +24,7 @@ ORDERS = {"index": 0, "canonical": 1}
 PROBE_MODES = {"axes": 0, "table": 1, "seeded": 2}
 
 EXPORTS = ("f3d_params_default", "f3d_max_buckets", "f3d_workspace_bytes", "f3d_psh_bucketize", "f3d_psh_bucketize_static",
-           "f3d_bucket_swin_attn", "f3d_bucket_swin_attn_f16", "f3d_attn_bwd_workspace_bytes", "f3d_bucket_swin_attn_bwd", "f3d_ln_linear", "f3d_pool_max_rows", "f3d_pool_workspace_bytes", "f3d_inbucket_pool",
+           "f3d_bucket_swin_attn", "f3d_bucket_swin_attn_f16", "f3d_attn_block_rows", "f3d_attn_bwd_workspace_bytes", "f3d_bucket_swin_attn_bwd", "f3d_ln_linear", "f3d_pool_max_rows", "f3d_pool_workspace_bytes", "f3d_inbucket_pool",
            "f3d_unpermute", "f3d_error_string", "f3d_last_hip_error", "f3d_version")
 POOL_OPS = {"sum": 0, "mean": 1, "min": 2, "max": 3}
 
@@ -74,6 +74,8 @@ def lib() -> ctypes.CDLL:
         L.f3d_bucket_swin_attn.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i64, i32, i32, i32, i32, i32, i32, i32, f32, vp, vp, vp, vp]
         L.f3d_bucket_swin_attn.restype = ctypes.c_int
         L.f3d_bucket_swin_attn_f16.argtypes = L.f3d_bucket_swin_attn.argtypes
+        L.f3d_attn_block_rows.argtypes = [i64, i64, i32, i32, i32, i32, i32, i32]
+        L.f3d_attn_block_rows.restype = ctypes.c_int
         L.f3d_bucket_swin_attn_f16.restype = ctypes.c_int
         L.f3d_attn_bwd_workspace_bytes.argtypes = [i64, i32, ctypes.POINTER(ctypes.c_size_t)]
         L.f3d_attn_bwd_workspace_bytes.restype = ctypes.c_int
@@ -269,6 +271,15 @@ def bucket_swin_attn(q, k, v, buckets: Buckets, heads: int, head_dim: int, mode:
     if rc != F3D_OK:
         raise Flash3DError(rc, "f3d_bucket_swin_attn")
     return out
+
+
+def attn_block_rows(buckets: "Buckets", heads: int, head_dim: int, mode: str = "plain", stride: int = 2) -> int:
+    """f3d_attn_block_rows: query rows per workgroup (128 or 256) the attention kernel uses on this layout."""
+    r = int(lib().f3d_attn_block_rows(buckets.n_scans, buckets.max_buckets, buckets.bucket_cap, buckets.scope_buckets,
+                                      MODES[mode] if isinstance(mode, str) else mode, stride, heads, head_dim))
+    if r < 0:
+        raise Flash3DError(r, "f3d_attn_block_rows")
+    return r
 
 
 def bucket_swin_attn_bwd(q, k, v, out, dout, lse, buckets: Buckets, heads: int, head_dim: int, mode: str = "plain",

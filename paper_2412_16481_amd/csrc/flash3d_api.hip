@@ -414,6 +414,17 @@ static int attn_forward(int f16, const void* q, const void* k, const void* v, co
     return e == hipSuccess ? F3D_OK : hip_fail(e);
 }
 
+int f3d_attn_block_rows(int64_t n_scans, int64_t max_buckets, int32_t bucket_cap, int32_t scope_buckets, int32_t mode,
+                        int32_t stride, int32_t heads, int32_t head_dim)
+{
+    if (n_scans < 1 || max_buckets < 0 || bucket_cap < 1 || scope_buckets < 1 || heads < 1) return F3D_ERR_INVALID_ARG;
+    if (mode < F3D_PLAIN || mode > F3D_STRIDE || (mode == F3D_STRIDE && stride < 1)) return F3D_ERR_INVALID_ARG;
+    if (head_dim != 16 && head_dim != 32) return F3D_ERR_UNSUPPORTED;
+    const long long extra = mode == F3D_STRIDE ? stride + 1 : 2;
+    const long long slots = max_buckets / scope_buckets + extra * n_scans + 1;
+    return f3d::attn_block_rows(head_dim, slots, heads, bucket_cap);
+}
+
 int f3d_bucket_swin_attn(const void* q, const void* k, const void* v, const int32_t* perm, const int32_t* offsets,
                          const int32_t* scan_bucket_start, int64_t n, int32_t n_scans, int64_t max_buckets,
                          int32_t bucket_cap, int32_t scope_buckets, int32_t mode, int32_t shift, int32_t stride, int32_t heads,

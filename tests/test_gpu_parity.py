@@ -327,8 +327,10 @@ def test_bucketize_variants_on_the_indoor_workload():
 def attn_case(q, k, v, bk, ref_layout, heads, d, mode, use_perm, rows=None, shift=2, stride=2, scale=0.0):
     """Run the GPU attention and the oracle on the same layout; compare all rows or the sampled ones."""
     n = q.shape[0]
-    out = f3d.bucket_swin_attn(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), bk, heads, d, mode,
-                               shift, stride, use_perm, scale)
+    # the output starts as NaN everywhere: a row that no workgroup wrote fails the finiteness check below
+    out = torch.full((n, heads * d), float("nan"), dtype=torch.bfloat16, device=DEV)
+    f3d.bucket_swin_attn(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), bk, heads, d, mode,
+                         shift, stride, use_perm, scale, out)
     torch.cuda.synchronize()
     got = out.float().cpu().numpy().astype(np.float64)
     sel = None
@@ -367,7 +369,47 @@ def test_attention_tiny_workload_all_rows():
     attn_case(q[perm], k[perm], v[perm], bk, ref, w.heads, w.head_dim, "shift", False)
 
 
-@pytest.mark.parametrize("name", ["indoor", "lidar4", "wide", "lidar8", "scope8k"])
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name", ["lidar4", "wide", "lidar8"])
+def test_attention_full_size_every_row(name):
+    """Configurations 3, 4 and 5 in the launch configuration bench.py times: EVERY row of every distinct pass against the
+    oracle (the oracle needs about 10-40 s per pass on the machine's host cores)."""
+    w = wl.make_workload(name)
+    bk, ref = check_bucketize(w.coords, w.batch_offsets, w.voxel_size, w.bucket_cap)
+    q, k, v = w.qkv()
+    bucket_major = name == "lidar8"                      # that workload runs its layers on bucket-major features
+    if bucket_major:
+        q, k, v = q[ref["perm"]], k[ref["perm"]], v[ref["perm"]]
+    for mode in dict.fromkeys(w.modes):
+        print(f"{name} {mode}: all {w.n} rows", flush=True)
+        attn_case(q, k, v, bk, ref, w.heads, w.head_dim, mode, not bucket_major)
+
+
+def big_ragged_layout():
+    """Four scans, 266 buckets of capacity 256 (scope 1024): full buckets mixed with short and one-row ones, scopes that
+    end inside a 32-row tile, a scan of a single short bucket. Large enough (67 scopes and more per pass) for the launch
+    to take two query tiles per wave with 8 heads."""
+    pat = [256, 256, 37, 256, 1, 256, 256, 256, 50, 256, 200, 256, 131, 256, 256, 7]
+    sizes = [(pat * 8)[:121], [17], [256] * 40 + [255, 256, 3, 256] * 11 + [90], [256, 129] * 30]
+    return hand_layout(sizes, 1024, 4)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("d", [16, 32])
+def test_attention_ragged_buckets_two_query_tiles_per_wave(d):
+    # all rows, all three patterns, with and without the permutation, on a launch of several thousand workgroups
+    heads = 8
+    bk, ref, n = big_ragged_layout()
+    assert f3d.attn_block_rows(bk, heads, d) == 256
+    rng = np.random.default_rng(34 + d)
+    q, k, v = (wl.f32_to_bf16_bits(rng.standard_normal((n, heads * d)).astype(np.float32)) for _ in range(3))
+    for mode, kw in (("plain", {}), ("shift", {"shift": 1}), ("shift", {"shift": 2}), ("stride", {"stride": 2}),
+                     ("stride", {"stride": 3})):
+        attn_case(q, k, v, bk, ref, heads, d, mode, True, **kw)
+        attn_case(q, k, v, bk, ref, heads, d, mode, False, **kw)
+
+
+@pytest.mark.parametrize("name", ["indoor", "scope8k"])
 def test_attention_full_size_sampled_rows(name):
     # the launch configuration bench.py times, on sampled query rows (each needs its whole scope in the oracle)
     w = wl.make_workload(name)
@@ -508,10 +550,10 @@ def attn_case_f16(q, k, v, bk, ref_layout, heads, d, mode, use_perm, rows=None, 
                   original_order=False):
     """q, k, v: numpy float16 arrays. The binary16 entry point against the oracle fed with the same bit patterns."""
     n = q.shape[0]
-    out = f3d.bucket_swin_attn(dev(q), dev(k), dev(v), bk, heads, d, mode, shift, stride, use_perm, scale,
-                               original_order=original_order)
+    out = torch.full((n, heads * d), float("nan"), dtype=torch.float16, device=DEV)   # an unwritten row stays NaN
+    f3d.bucket_swin_attn(dev(q), dev(k), dev(v), bk, heads, d, mode, shift, stride, use_perm, scale, out,
+                         original_order=original_order)
     torch.cuda.synchronize()
-    assert out.dtype == torch.float16
     got = out.float().cpu().numpy().astype(np.float64)
     if original_order:
         got = got[ref_layout["perm"]]
@@ -540,6 +582,20 @@ def test_attention_f16_ragged_buckets_all_modes(d, heads):
         attn_case_f16(q, k, v, bk, ref, heads, d, mode, True, **kw)
         attn_case_f16(q, k, v, bk, ref, heads, d, mode, False, **kw)
     attn_case_f16(q, k, v, bk, ref, heads, d, "shift", True, original_order=True)   # the store in input order
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("d", [16, 32])
+def test_attention_f16_ragged_buckets_two_query_tiles_per_wave(d):
+    heads = 8
+    bk, ref, n = big_ragged_layout()
+    assert f3d.attn_block_rows(bk, heads, d) == 256
+    rng = np.random.default_rng(64 + d)
+    q, k, v = (rng.standard_normal((n, heads * d)).astype(np.float16) for _ in range(3))
+    # (the oracle's binary16 decoder makes a pass cost 10-20 s here: one pass per pattern)
+    attn_case_f16(q, k, v, bk, ref, heads, d, "plain", True)
+    attn_case_f16(q, k, v, bk, ref, heads, d, "shift", False, shift=3)
+    attn_case_f16(q, k, v, bk, ref, heads, d, "stride", True, original_order=True)
 
 
 @pytest.mark.parametrize("name", ["tiny", "indoor", "lidar8"])
