@@ -2,14 +2,16 @@
 
 TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the benchmark's
 cpu-baseline leg. The product package never imports this module and this module never imports
-the product package. Arguments are numpy arrays; marshalling only, no arithmetic of the method.
+the product package. Arguments are numpy arrays. The C library holds the bucketing, the attention, its gradient and the
+pooling; two definitions are written here in numpy binary64 instead: the block glue (ln_linear) and the attention
+gradient as a function of the forward call's saved results (attn_bwd_saved).
 """
 from __future__ import annotations
 
 import ctypes
 import os
 import subprocess
-from typing import Dict, Optional
+from typing import Dict, List, Optional
 
 import numpy as np
 
@@ -184,6 +186,70 @@ def attn_bwd(q: np.ndarray, k: np.ndarray, v: np.ndarray, dout: np.ndarray, perm
     if r < 0:
         raise ValueError("orc_attn_bwd: bad arguments")
     return out
+
+
+def scope_rows(offsets: np.ndarray, scan_bucket_start: np.ndarray, scope_buckets: int, mode: str, shift: int = 2,
+               stride: int = 2) -> List[np.ndarray]:
+    """Bucket-major rows of every attention scope (Section 4.2), scope after scope, scan after scan: the buckets of a
+    scope in increasing order, each bucket's rows in order. The bucket -> scope map is group_of_bucket."""
+    off = np.asarray(offsets, dtype=np.int64)
+    sbs = np.asarray(scan_bucket_start, dtype=np.int64)
+    scopes: List[np.ndarray] = []
+    for b in range(sbs.shape[0] - 1):
+        members: Dict[int, List[np.ndarray]] = {}
+        for j in range(int(sbs[b + 1] - sbs[b])):
+            g = group_of_bucket(j, scope_buckets, mode, shift, stride)
+            members.setdefault(g, []).append(np.arange(off[sbs[b] + j], off[sbs[b] + j + 1]))
+        for g in sorted(members):
+            rows = np.concatenate(members[g])
+            if rows.size:
+                scopes.append(rows)
+    return scopes
+
+
+def attn_bwd_saved(q: np.ndarray, k: np.ndarray, v: np.ndarray, dout: np.ndarray, out: np.ndarray, lse: np.ndarray,
+                   perm: Optional[np.ndarray], offsets: np.ndarray, scan_bucket_start: np.ndarray, scope_buckets: int,
+                   mode: str, heads: int, head_dim: int, shift: int = 2, stride: int = 2, scale: Optional[float] = None,
+                   scope_sel: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+    """The gradient of the scope-restricted attention (Section 4.2) as a function of the forward call's SAVED results,
+    which is how a backward call is defined: with S = scale q k^T inside a scope,
+        P = exp(S - lse),  dP = dout v^T,  D = rowsum(dout o out),  dS = P o (dP - D),
+        dq = scale dS k,  dk = scale dS^T q,  dv = P^T dout,
+    `out` [n, C] and `lse` [n, heads] (natural log) being whatever the caller saved (binary64 arrays here; bucket-major
+    rows). With the exact output and log-sum-exp this is the plain gradient (attn_bwd); with a rounded `out` it is that
+    gradient's value for the rounded D. Binary64, numpy products per scope and head, nothing blocked or reordered.
+    q, k, v, dout: uint16 bf16 bit patterns, q/k/v read through perm as in attn. Returns dq, dk, dv [n, C] (bucket-major
+    rows, NaN where not computed), done [n], and the intermediates a tolerance derivation needs, per computed scope:
+    `scopes` = list of (rows, [per head: dict(P=, dS=, dP=, D=)])."""
+    qf, kf, vf, gf = (_bf16_bits_to_f64(np.ascontiguousarray(a, dtype=np.uint16)) for a in (q, k, v, dout))
+    if perm is not None:
+        pm = np.asarray(perm, dtype=np.int64)
+        qf, kf, vf = qf[pm], kf[pm], vf[pm]
+    of = np.asarray(out, dtype=np.float64)
+    lf = np.asarray(lse, dtype=np.float64)
+    n, C = qf.shape
+    sc = (1.0 / np.sqrt(float(head_dim))) if scale is None else float(scale)
+    res = {name: np.full((n, C), np.nan, dtype=np.float64) for name in ("dq", "dk", "dv")}
+    res["done"] = np.zeros(n, dtype=np.uint8)
+    res["scopes"] = []
+    for rows in scope_rows(offsets, scan_bucket_start, scope_buckets, mode, shift, stride):
+        if scope_sel is not None and not np.asarray(scope_sel)[rows].any():
+            continue
+        per_head = []
+        for h in range(heads):
+            sl = slice(h * head_dim, (h + 1) * head_dim)
+            Q, K, V, G, O = qf[rows, sl], kf[rows, sl], vf[rows, sl], gf[rows, sl], of[rows, sl]
+            P = np.exp(sc * (Q @ K.T) - lf[rows, h][:, None])
+            dP = G @ V.T
+            D = (G * O).sum(axis=1)
+            dS = P * (dP - D[:, None])
+            res["dq"][rows, sl] = sc * (dS @ K)
+            res["dk"][rows, sl] = sc * (dS.T @ Q)
+            res["dv"][rows, sl] = P.T @ G
+            per_head.append(dict(P=P, dS=dS, dP=dP, D=D))
+        res["done"][rows] = 1
+        res["scopes"].append((rows, per_head))
+    return res
 
 
 def unpermute(src: np.ndarray, perm: np.ndarray) -> np.ndarray:

@@ -152,3 +152,70 @@ def test_scope_selection_and_forward_consistency():
     v = wl.bf16_bits_to_f32(vb).astype(np.float64)
     g = wl.bf16_bits_to_f32(gb).astype(np.float64)
     np.testing.assert_allclose((full["dv"] * v).sum(), (out * g).sum(), rtol=1e-12)
+
+
+# ----------------------------------------------------------------------------- the gradient from saved forward results
+
+
+def test_scope_rows_reproduces_the_worked_example_of_section_4_2():
+    # eight buckets of two rows, four buckets per scope: plain {0-3},{4-7}; shifted by two {0,1},{2-5},{6,7};
+    # every second bucket {0,2,4,6},{1,3,5,7}
+    off = np.arange(0, 18, 2)
+    sbs = np.array([0, 8])
+    buckets = lambda scopes: [sorted(set((r // 2).tolist())) for r in scopes]
+    assert buckets(oracle.scope_rows(off, sbs, 4, "plain")) == [[0, 1, 2, 3], [4, 5, 6, 7]]
+    assert buckets(oracle.scope_rows(off, sbs, 4, "shift", shift=2)) == [[0, 1], [2, 3, 4, 5], [6, 7]]
+    assert buckets(oracle.scope_rows(off, sbs, 4, "stride", stride=2)) == [[0, 2, 4, 6], [1, 3, 5, 7]]
+    # rows of a scope come bucket after bucket, and the scopes of a pass partition the rows
+    allrows = np.concatenate(oracle.scope_rows(off, sbs, 4, "stride", stride=2))
+    assert sorted(allrows.tolist()) == list(range(16))
+
+
+@pytest.mark.parametrize("mode,kw", [("plain", {}), ("shift", {"shift": 1}), ("stride", {"stride": 3})])
+@pytest.mark.parametrize("use_perm", [False, True])
+def test_gradient_from_exact_saved_results_is_the_plain_gradient(mode, kw, use_perm):
+    """D = rowsum(dO o O) and P = exp(S - lse) with the exact O and lse give the gradient of the definition: two different
+    formulas (the C oracle sums P o dP and normalises its own softmax) must agree to rounding."""
+    off, sbs = layout([[16, 16, 9, 16, 1, 16, 16], [5], [16, 16, 16, 16, 16, 16, 16, 16, 3]])
+    n, heads, d, m = int(off[-1]), 3, 16, 4
+    rng = np.random.default_rng(70)
+    q, k, v, g = (wl.f32_to_bf16_bits(rng.standard_normal((n, heads * d)).astype(np.float32)) for _ in range(4))
+    perm = rng.permutation(n).astype(np.int32) if use_perm else None
+    want = oracle.attn_bwd(q, k, v, g, perm, off, sbs, m, mode, heads, d, **kw)
+    out = oracle.attn(q, k, v, perm, off, sbs, m, mode, heads, d, **kw)
+    got = oracle.attn_bwd_saved(q, k, v, g, out, want["lse"], perm, off, sbs, m, mode, heads, d, **kw)
+    assert got["done"].all()
+    for name in ("dq", "dk", "dv"):
+        assert np.abs(got[name] - want[name]).max() <= 1e-11 * max(1.0, np.abs(want[name]).max())
+    # a scope selection computes exactly the scopes of the flagged rows
+    sel = np.zeros(n, dtype=np.uint8)
+    sel[[0, n - 1]] = 1
+    part = oracle.attn_bwd_saved(q, k, v, g, out, want["lse"], perm, off, sbs, m, mode, heads, d, scope_sel=sel, **kw)
+    part_c = oracle.attn_bwd(q, k, v, g, perm, off, sbs, m, mode, heads, d, scope_sel=sel, **kw)
+    assert np.array_equal(part["done"], part_c["done"]) and 0 < part["done"].sum() < n
+    rows = part["done"].astype(bool)
+    assert np.allclose(part["dq"][rows], want["dq"][rows], rtol=0, atol=1e-11)
+
+
+def test_a_change_of_the_saved_output_moves_dq_and_dk_through_D_only():
+    """dq, dk are affine in the saved output: out + E changes D by rowsum(dO o E) and leaves dv alone,
+    dq_i -> dq_i - scale * dD_i * sum_j P_ij k_j."""
+    off, sbs = layout([[16, 16, 7]])
+    n, heads, d, m = int(off[-1]), 2, 16, 4
+    rng = np.random.default_rng(71)
+    q, k, v, g = (wl.f32_to_bf16_bits(rng.standard_normal((n, heads * d)).astype(np.float32)) for _ in range(4))
+    out = oracle.attn(q, k, v, None, off, sbs, m, "plain", heads, d)
+    lse = oracle.attn_bwd(q, k, v, g, None, off, sbs, m, "plain", heads, d)["lse"]
+    base = oracle.attn_bwd_saved(q, k, v, g, out, lse, None, off, sbs, m, "plain", heads, d)
+    E = rng.standard_normal(out.shape) * 1e-2
+    moved = oracle.attn_bwd_saved(q, k, v, g, out + E, lse, None, off, sbs, m, "plain", heads, d)
+    assert np.array_equal(moved["dv"], base["dv"])
+    kf = wl.bf16_bits_to_f32(k).astype(np.float64)
+    gf = wl.bf16_bits_to_f32(g).astype(np.float64)
+    scale = 1.0 / np.sqrt(d)
+    (rows, per_head), = base["scopes"]
+    for h in range(heads):
+        sl = slice(h * d, (h + 1) * d)
+        dD = (gf[:, sl] * E[:, sl]).sum(axis=1)
+        expect = base["dq"][:, sl] - scale * dD[:, None] * (per_head[h]["P"] @ kf[:, sl])
+        assert np.abs(moved["dq"][:, sl] - expect).max() <= 1e-12
