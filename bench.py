@@ -430,8 +430,10 @@ def main() -> int:
     if args.ceilings:
         res["ceilings"] = measured_ceilings(d)
     cpu_rows = args.cpu_rows
-    if cpu_rows < 0:   # the whole indoor workload costs about 20 s on 8 cores; keep other workloads to the same work
-        cpu_rows = int(min(n, 2.6e13 / (w.bucket_cap * C * len(w.modes))))
+    if cpu_rows < 0:
+        # The oracle's attention costs about scope * C multiply-adds (binary64, QK^T and PV) per query row and pass and
+        # runs at roughly 9e9 of them per second on 16 host threads: sample as many rows as about 20 s pay for.
+        cpu_rows = int(min(n, 1.8e11 / (w.bucket_cap * C * len(w.modes))))
     if cpu_rows > 0:
         res["cpu_baseline"] = cpu_baseline(w, cpu_rows)
     print(json.dumps(res))
