@@ -80,32 +80,47 @@ def cpu_baseline(w, sample_rows: int):
 
 def measured_ceilings(head_dim: int) -> dict:
     """What this GPU sustains on the attention kernel's instruction mix with no memory traffic (register-only
-    loops, random operand bits), best over 1..8 waves per SIMD: the matrix core alone, the exponential + bf16-pack
-    work of the softmax alone, and the head_dim-16 tile loop (two score MFMAs, 16 exp, 8 packs, two P V MFMAs)."""
+    loops, random operand bits), best over 1..8 waves per SIMD, as score elements (1024 per 32x32 tile) per second
+    and as nanoseconds per tile and SIMD: the matrix core alone, the softmax's vector work alone, the tile loops
+    written serially and software-pipelined as the kernel issues them, and the vector and matrix streams of a
+    head_dim-32 tile with no data dependence between them."""
     import ctypes
 
     import torch  # noqa: F401  (the HIP runtime that is already loaded)
     mb = ctypes.CDLL(os.path.join(ROOT, "paper_2412_16481_amd", "libf3d_microbench.so"))
     mb.f3d_mb_run.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)]
-    best = {}
-    for kind, name in ((0, "mfma_only"), (1, "softmax_only"), (2, "tile_loop")):
+    kinds = ((0, "mfma_only"), (1, "softmax_only"), (2, "tile_loop"), (3, "pipelined_tile_d32"), (4, "pipelined_tile_d16"),
+             (5, "vector_part_d32"), (6, "six_mfma_per_tile"), (7, "vector_and_six_mfma_independent"))
+    best, single = {}, {}
+    for kind, name in kinds:
         for wps in (1, 2, 3, 4, 5, 6, 8):
             ms, work = ctypes.c_float(0), ctypes.c_double(0)
             rc = mb.f3d_mb_run(kind, wps, ctypes.byref(ms), ctypes.byref(work))
             if rc != 0:
                 raise RuntimeError(f"f3d_mb_run failed: hipError {rc}")
             rate = work.value / (ms.value * 1e-3)
+            if wps == 1:
+                single[name] = rate
             if name not in best or rate > best[name][0]:
                 best[name] = (rate, wps)
-    flop_per_elem = 4.0 * head_dim   # QK^T and PV, per score element
-    return {
+    sm = torch.cuda.get_device_properties(0).multi_processor_count * 4   # SIMDs
+
+    def ns_per_tile(rate):   # elements/s over the whole GPU -> ns per 1024-element tile on one SIMD
+        return 1024.0 * sm / rate * 1e9
+
+    res = {
         "mfma_only_tflops": best["mfma_only"][0] / 1e12, "mfma_only_waves_per_simd": best["mfma_only"][1],
         "softmax_only_gelem_per_s": best["softmax_only"][0] / 1e9,
-        "softmax_only_as_attention_tflops": best["softmax_only"][0] * flop_per_elem / 1e12,
+        "softmax_only_as_attention_tflops": best["softmax_only"][0] * 4.0 * head_dim / 1e12,
         "tile_loop_gelem_per_s": best["tile_loop"][0] / 1e9, "tile_loop_waves_per_simd": best["tile_loop"][1],
         "tile_loop_as_attention_tflops_d16": best["tile_loop"][0] * 64.0 / 1e12,
+        "pipelined_tile_d32_as_attention_tflops": best["pipelined_tile_d32"][0] * 128.0 / 1e12,
+        "pipelined_tile_d16_as_attention_tflops": best["pipelined_tile_d16"][0] * 64.0 / 1e12,
+        "ns_per_tile_and_simd": {name: {"best": ns_per_tile(best[name][0]), "waves_per_simd": best[name][1],
+                                        "one_wave": ns_per_tile(single[name])} for _, name in kinds[1:]},
         "note": "register-only loops, random operand bits, best over 1..8 waves per SIMD; elements = score elements",
     }
+    return res
 
 
 def main() -> int:

@@ -5,6 +5,14 @@
 //   kind 2: tile loop        the head_dim-16 tile of Bucket-Swin attention (Section 4.2) in registers: two MFMAs
 //                            for the scaled scores (bf16 head + remainder of q), 16 exponentials, 8 packs, two
 //                            MFMAs for P V
+//   kind 3: pipelined tile, head_dim 32   the tile loop as the attention kernel issues it: the four score MFMAs of
+//                            the NEXT tile between groups of four exponentials of the current one, then packs,
+//                            8 dot2 (softmax denominator) and the two P V MFMAs; order pinned by scheduling barriers
+//   kind 4: pipelined tile, head_dim 16   the same with two score MFMAs and no dot2
+//   kind 5: vector part only of kind 3 (16 exp, 8 packs, 8 dot2)
+//   kind 6: six accumulating MFMAs per tile on three independent accumulators, nothing else
+//   kind 7: kinds 5 and 6 in one loop, with no data dependence between the vector and the matrix work: what the two
+//           units cost each other when nothing but issue and register ports couple them
 // Operands hold random bits: the clock this GPU sustains depends on the data. Built into its own library
 // (libf3d_microbench.so); bench.py --ceilings runs it. Not part of the product path.
 #include <hip/hip_runtime.h>
@@ -30,7 +38,14 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
     return *reinterpret_cast<uint32_t*>(&y);
 }
 
-constexpr int ITER = 4096;   // tiles (kind 1, 2) or groups of four MFMAs (kind 0) per wave
+constexpr int ITER = 4096;   // tiles (kinds 1..7) or groups of four MFMAs (kind 0) per wave
+#define MB_SB() __builtin_amdgcn_sched_barrier(0)
+
+__device__ __forceinline__ float sum2(uint32_t pair, float c)
+{
+    const uint32_t ones = 0x3F803F80u;
+    return __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<const bf16x2*>(&pair), *reinterpret_cast<const bf16x2*>(&ones), c, false);
+}
 
 template <int KIND>
 __global__ __launch_bounds__(256) void k_ceiling(const uint32_t* __restrict__ seed, float* __restrict__ sink, float mul)
@@ -73,6 +88,92 @@ __global__ __launch_bounds__(256) void k_ceiling(const uint32_t* __restrict__ se
             }
         }
         for (int i = 0; i < 16; ++i) t += s[i];
+    } else if (KIND == 3 || KIND == 4) {
+        constexpr bool D32 = KIND == 3;
+        f32x16 sa = {0}, sb = {0};
+        float l2 = 0.f;
+        sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(K.b, Q.b, sa, 0, 0, 0);
+        auto unit = [&](f32x16& s, f32x16& sn, int it) __attribute__((always_inline)) {
+            K.u[0] ^= (uint32_t)it & 0x00010001u;
+            MB_SB();
+#pragma unroll
+            for (int r = 0; r < 4; ++r) s[r] = __builtin_amdgcn_exp2f(s[r]);
+            MB_SB();
+            sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(K.b, Q.b, f32x16{0}, 0, 0, 0);
+            MB_SB();
+#pragma unroll
+            for (int r = 4; r < 8; ++r) s[r] = __builtin_amdgcn_exp2f(s[r]);
+            MB_SB();
+            if (D32) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(K.b, Q2.b, sn, 0, 0, 0);
+            MB_SB();
+#pragma unroll
+            for (int r = 8; r < 12; ++r) s[r] = __builtin_amdgcn_exp2f(s[r]);
+            MB_SB();
+            sn = D32 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(V0.b, Q.b, sn, 0, 0, 0) : __builtin_amdgcn_mfma_f32_32x32x16_bf16(K.b, Q2.b, sn, 0, 0, 0);
+            MB_SB();
+#pragma unroll
+            for (int r = 12; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(s[r]);
+            MB_SB();
+            if (D32) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(V0.b, Q2.b, sn, 0, 0, 0);
+            MB_SB();
+            Frag p0, p1;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) p0.u[e] = pack_bf16(s[2 * e], s[2 * e + 1]);
+            if (D32) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { if (e & 1) l2 = sum2(p0.u[e], l2); else t = sum2(p0.u[e], t); }
+            }
+            MB_SB();
+            o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(V0.b, p0.b, o, 0, 0, 0);
+            MB_SB();
+#pragma unroll
+            for (int e = 0; e < 4; ++e) p1.u[e] = pack_bf16(s[8 + 2 * e], s[9 + 2 * e]);
+            if (D32) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { if (e & 1) l2 = sum2(p1.u[e], l2); else t = sum2(p1.u[e], t); }
+            }
+            MB_SB();
+            o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(V1.b, p1.b, o, 0, 0, 0);
+            MB_SB();
+        };
+        for (int it = 0; it < ITER; it += 2) { unit(sa, sb, it); unit(sb, sa, it + 1); }
+        for (int i = 0; i < 16; ++i) t += sa[i] + sb[i];
+        t += l2;
+    } else if (KIND >= 5) {
+        // the vector stream and the matrix stream share no register: only issue slots and register ports couple them
+        f32x16 s, c1 = {0}, c2 = {0};
+        float l2 = 0.f;
+        for (int i = 0; i < 16; ++i) s[i] = (float)(lane + i) * mul;
+        for (int it = 0; it < ITER; ++it) {
+            K.u[0] ^= (uint32_t)it & 0x00010001u;
+#pragma unroll
+            for (int n = 0; n < 6; ++n) {
+                MB_SB();
+                if (KIND != 6) {
+                    if (n < 4) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) s[4 * n + r] = __builtin_amdgcn_exp2f(s[4 * n + r]);
+                    } else {
+                        Frag p;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) p.u[e] = pack_bf16(s[8 * (n - 4) + 2 * e], s[8 * (n - 4) + 2 * e + 1]);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) { if (e & 1) l2 = sum2(p.u[e], l2); else t = sum2(p.u[e], t); }
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) s[8 * (n - 4) + 2 * e] = __uint_as_float(p.u[e] & 0x3FFF0000u);   // nothing dead, nothing grows
+                    }
+                }
+                MB_SB();
+                if (KIND != 5) {
+                    if (n % 3 == 0) o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(K.b, Q.b, o, 0, 0, 0);
+                    else if (n % 3 == 1) c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(V0.b, Q2.b, c1, 0, 0, 0);
+                    else c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(V1.b, Q.b, c2, 0, 0, 0);
+                }
+                MB_SB();
+            }
+        }
+        for (int i = 0; i < 16; ++i) t += s[i] + c1[i] + c2[i];
+        t += l2;
     } else {
         for (int it = 0; it < ITER; ++it) {
             K.u[0] ^= (uint32_t)it & 0x00010001u;
@@ -98,11 +199,11 @@ __global__ __launch_bounds__(256) void k_ceiling(const uint32_t* __restrict__ se
 }  // namespace
 
 // Runs one kind with `waves_per_simd` (1..8) waves on every SIMD of the current device and writes the duration of
-// one launch in milliseconds and the work it did (MFMA FLOP for kind 0, score elements for kinds 1 and 2).
+// one launch in milliseconds and the work it did (MFMA FLOP for kind 0, score elements = 1024 per tile for the others).
 // Returns 0, or a hipError_t value. Allocates and frees its own small buffers; not for use inside a timed region.
 extern "C" int f3d_mb_run(int kind, int waves_per_simd, float* ms_out, double* work_out)
 {
-    if (kind < 0 || kind > 2 || waves_per_simd < 1 || waves_per_simd > 8 || !ms_out || !work_out) return (int)hipErrorInvalidValue;
+    if (kind < 0 || kind > 7 || waves_per_simd < 1 || waves_per_simd > 8 || !ms_out || !work_out) return (int)hipErrorInvalidValue;
     int dev = 0, cus = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
@@ -122,9 +223,16 @@ extern "C" int f3d_mb_run(int kind, int waves_per_simd, float* ms_out, double* w
     if (e == hipSuccess) {
         for (int rep = 0; rep < 2 && e == hipSuccess; ++rep) {   // the first launch warms up
             e = hipEventRecord(a, nullptr);
-            if (kind == 0) k_ceiling<0><<<blocks, 256>>>(seed, sink, 0.001f);
-            else if (kind == 1) k_ceiling<1><<<blocks, 256>>>(seed, sink, 0.001f);
-            else k_ceiling<2><<<blocks, 256>>>(seed, sink, 0.001f);
+            switch (kind) {
+                case 0: k_ceiling<0><<<blocks, 256>>>(seed, sink, 0.001f); break;
+                case 1: k_ceiling<1><<<blocks, 256>>>(seed, sink, 0.001f); break;
+                case 2: k_ceiling<2><<<blocks, 256>>>(seed, sink, 0.001f); break;
+                case 3: k_ceiling<3><<<blocks, 256>>>(seed, sink, 0.001f); break;
+                case 4: k_ceiling<4><<<blocks, 256>>>(seed, sink, 0.001f); break;
+                case 5: k_ceiling<5><<<blocks, 256>>>(seed, sink, 0.001f); break;
+                case 6: k_ceiling<6><<<blocks, 256>>>(seed, sink, 0.001f); break;
+                default: k_ceiling<7><<<blocks, 256>>>(seed, sink, 0.001f); break;
+            }
             if (e == hipSuccess) e = hipEventRecord(b, nullptr);
             if (e == hipSuccess) e = hipEventSynchronize(b);
         }

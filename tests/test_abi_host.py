@@ -33,7 +33,7 @@ def test_microbenchmark_library_is_built_and_refuses_bad_arguments_on_the_host()
     mb = ctypes.CDLL(os.path.join(ROOT, "paper_2412_16481_amd", "libf3d_microbench.so"))
     mb.f3d_mb_run.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)]
     ms, work = ctypes.c_float(0), ctypes.c_double(0)
-    assert mb.f3d_mb_run(3, 4, ctypes.byref(ms), ctypes.byref(work)) != 0
+    assert mb.f3d_mb_run(8, 4, ctypes.byref(ms), ctypes.byref(work)) != 0
     assert mb.f3d_mb_run(0, 0, ctypes.byref(ms), ctypes.byref(work)) != 0
     assert mb.f3d_mb_run(0, 9, ctypes.byref(ms), ctypes.byref(work)) != 0
     assert mb.f3d_mb_run(0, 4, None, ctypes.byref(work)) != 0
