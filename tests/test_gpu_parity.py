@@ -324,7 +324,7 @@ def test_bucketize_variants_on_the_indoor_workload():
 # ----------------------------------------------------------------------------- attention
 
 
-def attn_case(q, k, v, bk, ref_layout, heads, d, mode, use_perm, rows=None, shift=2, stride=2, scale=0.0):
+def attn_case(q, k, v, bk, ref_layout, heads, d, mode, use_perm, rows=None, shift=2, stride=2, scale=0.0, atol=ATOL):
     """Run the GPU attention and the oracle on the same layout; compare all rows or the sampled ones."""
     n = q.shape[0]
     # the output starts as NaN everywhere: a row that no workgroup wrote fails the finiteness check below
@@ -343,7 +343,7 @@ def attn_case(q, k, v, bk, ref_layout, heads, d, mode, use_perm, rows=None, shif
     mask = slice(None) if rows is None else rows
     err = np.abs(got[mask] - ref[mask])
     assert np.isfinite(got).all()
-    assert err.max() <= ATOL, f"max-abs {err.max():.4g} (mean {err.mean():.3g})"
+    assert err.max() <= atol, f"max-abs {err.max():.4g} (mean {err.mean():.3g})"
     return got, err.max()
 
 
@@ -493,6 +493,66 @@ def test_attention_every_score_far_below_zero(d):
         attn_case(q, k, v, bk, ref, heads, d, mode, True, scale=0.25)
     attn_case_f16(wl.bf16_bits_to_f32(q).astype(np.float16), wl.bf16_bits_to_f32(k).astype(np.float16),
                   wl.bf16_bits_to_f32(v).astype(np.float16), bk, ref, heads, d, "plain", True, scale=0.25)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("d", [16, 32])
+def test_attention_running_maximum_sweep_on_two_query_tiles_per_wave(d):
+    """The checked fallback (scores outside the window of the sweep against the fixed reference) on the large ragged
+    layout, i.e. on the kernels that keep two query tiles per wave: q and k of standard deviation 4 give scores of
+    +-100 and more in log2 units for some rows of nearly every scope; a second case has every score far below zero
+    (first tile of the running-maximum sweep meets a maximum below -128). bf16 and binary16."""
+    heads = 8
+    bk, ref, n = big_ragged_layout()
+    assert f3d.attn_block_rows(bk, heads, d) == 256
+    rng = np.random.default_rng(44 + d)
+    q, k = (wl.f32_to_bf16_bits((4.0 * rng.standard_normal((n, heads * d))).astype(np.float32)) for _ in range(2))
+    v = wl.f32_to_bf16_bits(rng.standard_normal((n, heads * d)).astype(np.float32))
+    # a softmax this peaked returns single V rows: the bound is the relative one of the large-values test below
+    # (rounding of the output and of a dominating probability), 1.25 * 2^-8 * max|v|
+    vmax = float(np.abs(wl.bf16_bits_to_f32(v)).max())
+    peaked = 1.25 * 2.0 ** -8 * vmax
+    attn_case(q, k, v, bk, ref, heads, d, "shift", True, atol=peaked)
+    attn_case(q, k, v, bk, ref, heads, d, "stride", False, stride=3, atol=peaked)
+    ql = wl.f32_to_bf16_bits(np.full((n, heads * d), 8.0, np.float32))
+    kl = wl.f32_to_bf16_bits((-8.0 + 0.25 * rng.standard_normal((n, heads * d))).astype(np.float32))
+    attn_case(ql, kl, v, bk, ref, heads, d, "plain", True, scale=0.25)
+    attn_case_f16(wl.bf16_bits_to_f32(q).astype(np.float16), wl.bf16_bits_to_f32(k).astype(np.float16),
+                  wl.bf16_bits_to_f32(v).astype(np.float16), bk, ref, heads, d, "shift", True,
+                  atol=max(ATOL_F16, 1.25 * 2.0 ** -11 * vmax))
+
+
+def test_attention_two_term_query_at_very_large_norms():
+    """The scale is folded into q as two bf16 terms, so a scaled score is exact to about 2^-16 of sum_c |q_c k_c| scale
+    (not of the score). The header states the size of the effect: with |q||k| scale near 10^4 single outputs move by a
+    few 10^-2 where two top scores lie within a unit of each other, and the log-sum-exp by up to about 0.1. This pins
+    that statement: outputs finite, within 0.06 of the oracle everywhere, within 1e-2 for all but a small share of the
+    elements, lse within 2^-15 of sum_c |q_c||k_c| scale maximised over the scope, plus the 4e-3 of the probabilities'
+    rounding."""
+    bk, ref, n = hand_layout([[64, 64, 64, 64, 64, 64, 64, 40]], 256, 4)
+    rng = np.random.default_rng(45)
+    heads, d = 2, 32
+    # common offsets make |q||k| large while the score differences stay moderate: q = 40 + N(0,1), k = 8 + N(0, 0.02)
+    q = wl.f32_to_bf16_bits((40.0 + rng.standard_normal((n, heads * d))).astype(np.float32))
+    k = wl.f32_to_bf16_bits((8.0 + 0.02 * rng.standard_normal((n, heads * d))).astype(np.float32))
+    v = wl.f32_to_bf16_bits(rng.standard_normal((n, heads * d)).astype(np.float32))
+    scale = 1.0
+    qf, kf = wl.bf16_bits_to_f32(q).astype(np.float64), wl.bf16_bits_to_f32(k).astype(np.float64)
+    norm = float((np.abs(qf[:, :d]).sum(axis=1).max()) * np.abs(kf[:, :d]).max() * scale)
+    assert 5e3 < norm < 5e4                                   # the regime the header talks about
+    lse = torch.empty(n, heads, dtype=torch.float32, device=DEV)
+    out = f3d.bucket_swin_attn(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), bk, heads, d, "plain",
+                               2, 2, True, scale, lse=lse)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().astype(np.float64)
+    want = oracle.attn(q, k, v, ref["perm"], ref["offsets"], ref["scan_bucket_start"], 4, "plain", heads, d, 2, 2, scale)
+    ref_b = oracle.attn_bwd(q, k, v, v, ref["perm"], ref["offsets"], ref["scan_bucket_start"], 4, "plain", heads, d, 2, 2, scale)
+    err = np.abs(got - want)
+    assert np.isfinite(got).all()
+    assert err.max() <= 0.06, f"max-abs {err.max():.4g}"
+    assert (err > 1e-2).mean() <= 0.02, f"share above 1e-2: {(err > 1e-2).mean():.4g}"
+    lerr = np.abs(lse.cpu().numpy().astype(np.float64) - ref_b["lse"]).max()
+    assert lerr <= 4e-3 + 2.0 ** -15 * norm, f"lse error {lerr:.4g} at norm {norm:.4g}"
 
 
 def test_attention_large_values_meet_the_relative_bound():
