@@ -30,7 +30,7 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 # HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command, keyed by
 # workload; the figures and the commands are in profiles/k_attn_<workload>.md. A counter run cannot be made from
 # inside the timed run, so the line carries the stored figure and says where it comes from (None = not profiled).
-MEASURED_TRAFFIC_BYTES = {"indoor": 105.8e6, "lidar8": 1874.0e6}
+MEASURED_TRAFFIC_BYTES = {"indoor": 106.2e6, "lidar8": 1874.0e6}
 
 
 def scope_sizes(offsets: np.ndarray, sbs: np.ndarray, m: int, mode: str, shift: int, stride: int) -> np.ndarray:
