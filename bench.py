@@ -333,7 +333,7 @@ def main() -> int:
     if args.pool > 0:   # the stage's third operator, outside the headline step
         rho = args.pool
         pooled = f3d.inbucket_pool(coords, bk.perm, out, bo, 1024, rho, 0.1, args.hash, "mean")
-        pws = torch.empty(1 << 20, dtype=torch.uint8, device=dev)
+        pws = torch.empty(max(256, f3d.pool_workspace_bytes(n, w.n_scans, 1024)), dtype=torch.uint8, device=dev)
         torch.cuda.synchronize()
         n_out = int(pooled.pooled_offsets[-1])
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -352,6 +352,14 @@ def pool_max_rows(n: int, n_scans: int, tile: int, rho: int) -> int:
     return r
 
 
+def pool_workspace_bytes(n: int, n_scans: int, tile: int) -> int:
+    nb = ctypes.c_size_t(0)
+    rc = lib().f3d_pool_workspace_bytes(n, n_scans, tile, ctypes.byref(nb))
+    if rc != F3D_OK:
+        raise Flash3DError(rc, "f3d_pool_workspace_bytes")
+    return int(nb.value)
+
+
 def inbucket_pool(coords, perm, feat, batch_offsets, tile: int, rho: int, voxel_size: float, hash: str = "zorder_div",
                   op: str = "mean", workspace=None, out: Optional[Pooled] = None) -> Pooled:
     """f3d_inbucket_pool on torch CUDA tensors. coords float32 [n,3] (input order with perm, else bucket-major);

@@ -548,7 +548,9 @@ int f3d_pool_workspace_bytes(int64_t n, int32_t n_scans, int32_t tile, size_t* o
     if (!out_bytes) return F3D_ERR_INVALID_ARG;
     const int rc = check_pool(n, n_scans, tile, 1);
     if (rc != F3D_OK) return rc;
-    *out_bytes = align_up((size_t)(n / tile + n_scans) * sizeof(int4), 256);
+    const size_t tiles = (size_t)(n / tile + n_scans);
+    const size_t slots = tiles < (size_t)f3d::POOL_MAX_SLOTS ? tiles : (size_t)f3d::POOL_MAX_SLOTS;
+    *out_bytes = align_up(tiles * sizeof(int4), 256) + 256 + align_up(slots * f3d::pool_list_entries(tile) * 2, 256);
     return F3D_OK;
 }
 
@@ -594,6 +596,11 @@ int f3d_inbucket_pool(const float* coords, const int32_t* perm, const void* feat
     a.sub_of = sub_of;
     a.pooled_offsets = pooled_offsets;
     a.tile_info = (int4*)workspace;
+    a.tile_counter = (int*)((char*)workspace + align_up((size_t)a.n_tiles_ub * sizeof(int4), 256));
+    a.lists = (uint16_t*)((char*)a.tile_counter + 256);
+    a.list_cap = f3d::pool_list_entries(tile);
+    a.n_slots = a.n_tiles_ub < f3d::POOL_MAX_SLOTS ? a.n_tiles_ub : f3d::POOL_MAX_SLOTS;
+    a.ring_rows = (tile - (tile + rho - 1) / rho + 63) / 64 * 64;
     (void)hipGetLastError();
     const hipError_t e = f3d::pool_launch(a, (hipStream_t)stream);
     return e == hipSuccess ? F3D_OK : hip_fail(e);

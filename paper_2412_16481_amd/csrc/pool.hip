@@ -62,7 +62,10 @@ __global__ __launch_bounds__(1024) void k_pool_meta(PoolArgs a)
     __shared__ int lds[17];
     __shared__ int bad;
     const int tid = threadIdx.x;
-    if (tid == 0) bad = 0;
+    if (tid == 0) {
+        bad = 0;
+        *a.tile_counter = 0;
+    }
     __syncthreads();
     const int per_full = (a.tile + a.rho - 1) / a.rho;   // pooled rows of a full tile
     int tcarry = 0, ocarry = 0;
@@ -156,35 +159,182 @@ __device__ inline void tile_hash_cfg(int hash, int M, const int* vmax, ScanCfg& 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
-// dynamic LDS, kp = a.kp: px,py,pz [PT] floats | o4 [kp] float4 (x, y, z, -) | fill [kp] ints | wcnt [PW][kp] u16 |
-// open_list, id_of_hash, first_idx, ktot [kp] u16 each | members [PT + POOL_MAX_RHO] u16 | pick, rsub, rslot [PT] u16
+// ------------------------------------------------------------------------------------------------
+// The value of the lane whose number differs in bit log2(D), from data-parallel-primitive moves (inside a row of 16
+// lanes) and the lane-swap instructions (between rows and between halves): vector instructions only, where a shuffle
+// through the LDS crossbar would make the LDS pipeline the bottleneck of the sort below.
+template <int CTRL, int BANKS>
+__device__ __forceinline__ unsigned int dpp_mov(unsigned int old, unsigned int x)
+{
+    return (unsigned int)__builtin_amdgcn_update_dpp((int)old, (int)x, CTRL, 0xF, BANKS, false);
+}
+template <int D>
+__device__ __forceinline__ unsigned int lane_xor(unsigned int x, int lane)
+{
+    if (D == 1) return dpp_mov<0xB1, 0xF>(x, x);    // quad_perm [1,0,3,2]
+    if (D == 2) return dpp_mov<0x4E, 0xF>(x, x);    // quad_perm [2,3,0,1]
+    if (D == 4) return dpp_mov<0x124, 0xA>(dpp_mov<0x12C, 0x5>(x, x), x);   // row_ror 12 for lanes 0-3, 8-11; row_ror 4 for the others
+    if (D == 8) return dpp_mov<0x128, 0xF>(x, x);   // row_ror 8
+    if (D == 16) {
+        const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+        return (lane & 16) ? r[0] : r[1];
+    }
+    const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+    return (lane & 32) ? r[0] : r[1];
+}
+
+// Bitonic sort of 64 * NPL distinct 64-bit keys held by one wave, NPL per lane (element lane * NPL + r), ascending.
+// Strides below NPL stay inside a lane; larger ones exchange with the lane at distance stride / NPL. K is the length
+// of the runs being merged, J the stride of the step.
+template <int NPL, int K, int J>
+__device__ __forceinline__ void sort_step(unsigned long long (&key)[NPL], int lane)
+{
+    // direction of the run of K elements this element is in; the last phase sorts everything upwards
+    const bool lane_up = K >= 64 * NPL ? true : (lane & (K / NPL)) == 0;
+    if constexpr (J >= NPL) {
+        constexpr int LJ = J / NPL;
+        const bool keep_min = ((lane & LJ) == 0) == lane_up;
+#pragma unroll
+        for (int r = 0; r < NPL; ++r) {
+            const unsigned long long mine = key[r];
+            const unsigned int olo = lane_xor<LJ>((unsigned int)mine, lane);
+            const unsigned int ohi = lane_xor<LJ>((unsigned int)(mine >> 32), lane);
+            const unsigned long long other = ((unsigned long long)ohi << 32) | olo;
+            key[r] = ((mine < other) == keep_min) ? mine : other;
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < NPL; ++r) {
+            if (r & J) continue;
+            const bool up = K < NPL ? (r & K) == 0 : lane_up;
+            const unsigned long long x = key[r], y = key[r | J];
+            const bool swap = (x > y) == up;
+            key[r] = swap ? y : x;
+            key[r | J] = swap ? x : y;
+        }
+    }
+    if constexpr (J > 1) sort_step<NPL, K, J / 2>(key, lane);
+}
+template <int NPL, int K = 2>
+__device__ __forceinline__ void wave_sort_keys(unsigned long long (&key)[NPL], int lane)
+{
+    sort_step<NPL, K, K / 2>(key, lane);
+    if constexpr (K < 64 * NPL) wave_sort_keys<NPL, K * 2>(key, lane);
+}
+
+// One wave writes, for each of the rows left it is given (every PW-th), the ids of the open sub-buckets in the
+// order in which the row would choose them: increasing squared distance to the sub-bucket's first row, the lower id
+// first on a tie. The key is (bits of the distance, id): a squared distance is a non-negative binary32 number, whose
+// bit patterns are ordered like the numbers. `list` rows have `pitch` entries (a multiple of 8, >= nopen).
+template <int NPL>
+__device__ __forceinline__ void sort_choices(int nleft, int nopen, int pitch, const uint16_t* left_list, const float* px,
+                                             const float* py, const float* pz, const float4* o4, const uint16_t* open_list,
+                                             uint16_t* list, unsigned char* ring, int ring_rows)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int p = wave; p < nleft; p += PW) {
+        const int id = left_list[p];
+        const float qx = px[id], qy = py[id], qz = pz[id];
+        unsigned long long key[NPL];
+#pragma unroll
+        for (int r = 0; r < NPL; ++r) {   // the candidates' positions are read again for every row: registers are scarce
+            const int e = lane * NPL + r;
+            const float4 o = o4[min(e, nopen - 1)];
+            const float d2 = dist2(qx - o.x, qy - o.y, qz - o.z);
+            key[r] = e < nopen ? ((unsigned long long)__float_as_uint(d2) << 32) | open_list[e] : ~0ull;
+        }
+        wave_sort_keys<NPL>(key, lane);
+        unsigned int sid[NPL];   // padding entries (beyond nopen) become id 0: never chosen, but a valid index
+#pragma unroll
+        for (int r = 0; r < NPL; ++r) sid[r] = key[r] == ~0ull ? 0u : (unsigned int)key[r] & 0xFFFFu;
+        if (lane * NPL < 32) {   // the first four chunks of eight also go to the row's ring in LDS (chunk, row, 16 bytes)
+            unsigned int* dst = reinterpret_cast<unsigned int*>(ring + ((size_t)((lane * NPL) >> 3) * ring_rows + p) * 16 + ((lane * NPL) & 7) * 2);
+#pragma unroll
+            for (int r = 0; r < NPL; r += 2) dst[r >> 1] = sid[r] | (sid[r + 1] << 16);
+        }
+        if (lane * NPL < pitch) {
+            uint16_t* dst = list + (size_t)p * pitch + lane * NPL;
+            if (NPL == 8) {
+                *reinterpret_cast<uint4*>(dst) = make_uint4(sid[0] | (sid[1] << 16), sid[2] | (sid[3] << 16), sid[4] | (sid[5] << 16), sid[6] | (sid[7] << 16));
+            } else if (NPL == 4) {
+                *reinterpret_cast<uint2*>(dst) = make_uint2(sid[0] | (sid[1] << 16), sid[2] | (sid[3] << 16));
+            } else {
+                *reinterpret_cast<unsigned int*>(dst) = sid[0] | (sid[1] << 16);
+            }
+        }
+    }
+}
+
+// Workgroup barrier for steps that exchange data through LDS only: waits for this wave's LDS operations, not for
+// its global loads (__syncthreads() waits for both, and the rounds below keep a list prefetch in flight).
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// 16 bytes per lane from global memory straight into LDS: lane i's piece lands at byte address lds + 16 i (the
+// hardware adds the lane's offset to the base in M0). Not tracked by the compiler: the caller waits (vmcnt).
+__device__ __forceinline__ void lds_dma16(const void* g, uint32_t lds)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds), "v"(g) : "memory", "m0");
+}
+
+// entry `i` (0..7) of a chunk of eight 16-bit ids
+__device__ __forceinline__ int chunk_entry(const uint4& c, int i)
+{
+    // selects and a shift: indexing the four words by a variable would put the chunk into scratch memory
+    const unsigned long long lo = ((unsigned long long)c.y << 32) | c.x, hi = ((unsigned long long)c.w << 32) | c.z;
+    const unsigned long long half = (i & 4) ? hi : lo;
+    return (int)((half >> ((i & 3) << 4)) & 0xFFFFull);
+}
+
+// dynamic LDS, kp = a.kp: px,py,pz [PT] floats | o4 [kp] float4 (x, y, z, -) | fill [kp] ints | win [2][kp] ints |
+// open_list, id_of_hash, first_idx, ktot [kp] u16 each | members [PT + POOL_MAX_RHO] u16 | rsub, rslot [PT] u16 |
+// wcnt [PW][kp] u16, later reused as ring [4][ring_rows] of 16 bytes (the next 32 choices of every row left)
+//
+// Workgroups are persistent: each takes tiles from a counter until none is left, and owns one slot of the
+// choice-list area in global memory (its block index).
 __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __shared__ int lds[17];
     __shared__ uint32_t red[8];
     __shared__ ScanCfg cfg;
-    const int4 ti = a.tile_info[blockIdx.x];
-    const int n = ti.y;
-    if (n <= 0) return;
-    const int row0 = ti.x, out0 = ti.z;
+    __shared__ int next_tile;
+    __shared__ int rows_left;
+    __shared__ int more[2];
     const int rho = a.rho, kp = a.kp;
-    const int M = (n + rho - 1) / rho;
     const int tid = threadIdx.x, lane = tid & 63;
     float* px = reinterpret_cast<float*>(smem);
     float* py = px + PT;
     float* pz = py + PT;
     float4* o4 = reinterpret_cast<float4*>(pz + PT);   // first-row position of every open sub-bucket: one 16-byte read
     int* fill = reinterpret_cast<int*>(o4 + kp);
-    uint16_t* wcnt = reinterpret_cast<uint16_t*>(fill + kp);
-    uint16_t* open_list = wcnt + PW * kp;
+    int* win = fill + kp;                               // [2][kp] lowest contender of a sub-bucket, by parity of the pass
+    uint16_t* open_list = reinterpret_cast<uint16_t*>(win + 2 * kp);
     uint16_t* id_of_hash = open_list + kp;
     uint16_t* first_idx = id_of_hash + kp;
     uint16_t* ktot = first_idx + kp;
     uint16_t* members = ktot + kp;
-    uint16_t* pick = members + PT + POOL_MAX_RHO;   // [PT] choice of the t-th row left
-    uint16_t* rsub = pick + PT;                      // [PT] sub-bucket it joined (0xFFFF: none yet) and its slot
+    uint16_t* rsub = members + PT + POOL_MAX_RHO;    // [PT] sub-bucket the t-th row left joined, and its slot there
     uint16_t* rslot = rsub + PT;
+    uint16_t* wcnt = rslot + PT;                        // per-wave counters of the ranking by key (initial sub-buckets only)
+    unsigned char* ring = reinterpret_cast<unsigned char*>(wcnt);
+    const int ring_rows = a.ring_rows;
+    const uint32_t ring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)ring;   // LDS byte address
+    uint16_t* const my_lists = a.lists + (size_t)blockIdx.x * a.list_cap;
+
+  for (;;) {
+    __syncthreads();   // the tile before is done with LDS and with next_tile
+    if (tid == 0) next_tile = atomicAdd(a.tile_counter, 1);
+    __syncthreads();
+    const int tile_id = next_tile;
+    if (tile_id >= a.n_tiles_ub) break;
+    const int4 ti = a.tile_info[tile_id];
+    const int n = ti.y;
+    if (n <= 0) continue;
+    const int row0 = ti.x, out0 = ti.z;
+    const int M = (n + rho - 1) / rho;
 
     // ---- the tile's points, its minimum, voxel coordinates, voxel box
     const bool act = tid < n;
@@ -202,7 +352,11 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
     for (int k = tid; k < kp; k += PT) {
         fill[k] = 0;
         first_idx[k] = 0;
+        win[k] = 0x7FFFFFFF;
+        win[kp + k] = 0x7FFFFFFF;
     }
+    if (tid == 0) { more[0] = 0; more[1] = 0; }
+    rsub[tid] = (uint16_t)0xFFFF;
     __syncthreads();
     {
         uint32_t o[3] = {act ? f2ord(x) : 0xFFFFFFFFu, act ? f2ord(y) : 0xFFFFFFFFu, act ? f2ord(z) : 0xFFFFFFFFu};
@@ -266,174 +420,132 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
         fill[sub] = 1;
         first_idx[sub] = (uint16_t)tid;
     }
-    bool left = act && sub < 0;
+    const bool left0 = act && sub < 0;
     // ---- rounds: every row still left picks the open sub-bucket whose first row is nearest (state at the start of
-    //      the round); the contenders of a sub-bucket join in row order while it has room. While many rows are
-    //      left the whole workgroup takes the round (a row per thread). The long tail of rounds with at most 64
-    //      rows left is run by wave 0 alone, without workgroup barriers: its lanes hold the rows in row order.
-    int lpos = 0, nleft = 0, nopen = 0;
+    //      the round); the contenders of a sub-bucket join in row order while it has room. A sub-bucket never
+    //      reopens and its first row never changes, so the choices of a row over all rounds are one fixed sequence:
+    //      the sub-buckets open now, by (distance, id), of which the row takes the first that still has room. The
+    //      sequences are written once (a wave sorts one row's candidates at a time); a round is then a step along
+    //      them.
     uint16_t* left_list = members;   // [PT] thread ids of the rows still left, in row order (members is filled last)
-    for (int round = 0; round <= PT; ++round) {   // every round places at least one row; the bound is a safeguard
-        // one scan builds both lists: the rows still left (low half) and the sub-buckets with room (high half)
-        __syncthreads();   // the fill levels written by the steps above / the last round are in place
+    __syncthreads();                 // the fill levels written above are in place
+    int lpos, nleft, nopen;
+    {
         const bool open = tid < M && fill[tid] < rho;
         int tot;
-        const int pre = block_excl_scan((left ? 1 : 0) | (open ? 0x10000 : 0), &tot, lds);
+        const int pre = block_excl_scan((left0 ? 1 : 0) | (open ? 0x10000 : 0), &tot, lds);
         lpos = pre & 0xFFFF;
         nleft = tot & 0xFFFF;
         nopen = tot >> 16;
-        if (left) left_list[lpos] = (uint16_t)tid;
+        if (left0) left_list[lpos] = (uint16_t)tid;
         if (open) {
             const int f = first_idx[tid], opos = pre >> 16;
             open_list[opos] = (uint16_t)tid;
             o4[opos] = make_float4(px[f], py[f], pz[f], 0.f);
         }
+        if (tid == 0) rows_left = nleft;
         __syncthreads();
-        if (nleft <= 64) break;
-        // the rows left are spread over all threads again: g neighbouring lanes share one row's search
-        int g = 1;
-        while (g < 64 && nleft * g * 2 <= PT) g *= 2;
-        const int p = tid / g, part = tid - p * g;
-        float bd = __builtin_inff();
-        int bi = 0x7FFFFFFF;
-        if (p < nleft) {
-            const int id = left_list[p];
-            const float qx = px[id], qy = py[id], qz = pz[id];
-            // Lane `part` of the row's g lanes takes a contiguous range of the open list, in ascending order: the first
-            // candidate unconditionally, a later one only if strictly nearer (a tie keeps the lower sub-bucket id). Four
-            // candidates per trip, their reads issued together: the loop is bound by instruction issue and LDS latency.
-            const int chunk = (nopen + g - 1) / g;
-            int c = part * chunk;
-            const int cend = min(c + chunk, nopen);
-            if (c < cend) {
-                const float4 o = o4[c];
-                bd = dist2(qx - o.x, qy - o.y, qz - o.z);
-                bi = c;
-                ++c;
-                for (; c + 3 < cend; c += 4) {
-                    float4 v4[4];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) v4[u] = o4[c + u];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const float d2 = dist2(qx - v4[u].x, qy - v4[u].y, qz - v4[u].z);
-                        if (d2 < bd) { bd = d2; bi = c + u; }
-                    }
-                }
-                for (; c < cend; ++c) {
-                    const float4 v = o4[c];
-                    const float d2 = dist2(qx - v.x, qy - v.y, qz - v.z);
-                    if (d2 < bd) { bd = d2; bi = c; }
-                }
-            }
-        }
-        for (int d = g >> 1; d >= 1; d >>= 1) {   // smallest distance, the lower list position on a tie
-            const float od = __shfl_xor(bd, d, 64);
-            const int oi = __shfl_xor(bi, d, 64);
-            if (oi != 0x7FFFFFFF && (bi == 0x7FFFFFFF || od < bd || (od == bd && oi < bi))) { bd = od; bi = oi; }
-        }
-        if (p < nleft && part == 0) pick[p] = open_list[min(bi, nopen - 1)];
-        __syncthreads();
-        const bool dense = tid < nleft;   // thread t now speaks for the t-th row left: row order is kept
-        const int best = dense ? (int)pick[tid] : 0;
-        const int rank = block_rank_by_key(best, dense, keybits, M, wcnt, kp, nullptr);
-        const bool join = dense && fill[best] + rank < rho;
-        if (dense) {
-            rsub[tid] = join ? (uint16_t)best : (uint16_t)0xFFFF;
-            rslot[tid] = (uint16_t)(fill[best] + rank);
-        }
-        __syncthreads();   // every fill level has been read, every answer is written
-        if (join) atomicAdd(&fill[best], 1);
-        if (left && rsub[lpos] != 0xFFFF) {
-            sub = rsub[lpos];
-            slot = rslot[lpos];
-            left = false;
-        }
     }
-    if (nleft > 0 && nleft <= 64) {
-        // wave 0 takes the rows that are left (left_list, in row order) and the open list of this moment
-        uint16_t* tail_id = left_list;
-        uint16_t* res_sub = rsub;
-        uint16_t* res_slot = rslot;
-        if (tid < 64) {
-            const int L = nleft;
-            bool tl = lane < L;
-            const int me = tl ? (int)tail_id[lane] : 0;
-            const float qx0 = px[me], qy0 = py[me], qz0 = pz[me];
-            const unsigned long long lt = (1ull << lane) - 1ull;
-            int tsub = 0, tslot = 0, O = nopen;
-            for (int round = 0; round <= 64 && O > 0; ++round) {
-                const unsigned long long leftmask = __ballot(tl);
-                if (leftmask == 0ull) break;
-                // drop the sub-buckets that filled up (in place: a chunk is read before anything of it is overwritten)
-                int newO = 0;
-                for (int base = 0; base < O; base += 64) {
-                    const int c = base + lane;
-                    int s = 0;
-                    float4 co = make_float4(0.f, 0.f, 0.f, 0.f);
-                    bool keep = false;
-                    if (c < O) {
-                        s = open_list[c];
-                        co = o4[c];
-                        keep = fill[s] < rho;
-                    }
-                    const unsigned long long bal = __ballot(keep);
-                    if (keep) {
-                        const int p = newO + __popcll(bal & lt);
-                        open_list[p] = (uint16_t)s;
-                        o4[p] = co;
-                    }
-                    newO += __popcll(bal);
-                }
-                O = newO;
-                __threadfence_block();
-                if (O == 0) break;
-                // nearest open sub-bucket of this lane's row (ascending id: a tie keeps the lower one)
-                int mybest = 0;
-                if (tl) {
-                    const float4 o = o4[0];   // O > 0: the first candidate unconditionally, later ones if strictly nearer
-                    float bd = dist2(qx0 - o.x, qy0 - o.y, qz0 - o.z);
-                    int bj = 0;
-                    int c = 1;
-                    for (; c + 3 < O; c += 4) {   // four candidates per trip, reads first (as in the rounds above)
-                        float4 v4[4];
+    const int pitch = (nopen + 7) & ~7;
+    if (nleft > 0 && nopen > 0 && nleft <= ring_rows && (long long)nleft * pitch <= (long long)a.list_cap) {
+        if (nopen <= 128)
+            sort_choices<2>(nleft, nopen, pitch, left_list, px, py, pz, o4, open_list, my_lists, ring, ring_rows);
+        else if (nopen <= 256)
+            sort_choices<4>(nleft, nopen, pitch, left_list, px, py, pz, o4, open_list, my_lists, ring, ring_rows);
+        else
+            sort_choices<8>(nleft, nopen, pitch, left_list, px, py, pz, o4, open_list, my_lists, ring, ring_rows);
+        __threadfence_block();   // the lists are read by other waves of this workgroup
+        __syncthreads();
+        // Thread t now speaks for the t-th row left: row order is kept. It walks its list in chunks of eight entries.
+        // The chunk in use sits in registers; the row's ring in LDS holds it and the three after it. Entering chunk k,
+        // the thread asks for chunk k + 3 by a global->LDS load into the ring slot chunk k - 1 has left; such loads
+        // are waited for at the start of the next round, so a chunk asked for in an earlier round is there. A row
+        // that runs ahead of its requests (many closed sub-buckets in a row) reads its list from memory directly.
+        bool left = tid < nleft;
+        const uint4* mine = reinterpret_cast<const uint4*>(my_lists + (size_t)tid * pitch);
+        const int nchunks = pitch >> 3;
+        const int wave_u = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const uint4* ring_mine = reinterpret_cast<const uint4*>(ring) + tid;   // + q * ring_rows
+        uint4 cur = make_uint4(0, 0, 0, 0);
+        if (left) cur = ring_mine[0];
+        int have = min(4, nchunks);   // chunks 0 .. have - 1 have been asked for
+        int idx = 0, c = 0, par = 0;
+        for (int round = 0; round <= PT; ++round) {   // every round places at least one row; the bound is a safeguard
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the chunks asked for in the round before have arrived
+            bool contend = false;
+            if (left) {
+                for (;;) {   // the first sub-bucket of the sequence that still has room
+                    if (idx >= nopen) break;
+                    // all eight entries of the chunk are looked up together (their reads overlap, no branch per entry)
+                    const unsigned int w[4] = {cur.x, cur.y, cur.z, cur.w};
+                    unsigned int room = 0;
 #pragma unroll
-                        for (int u = 0; u < 4; ++u) v4[u] = o4[c + u];
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            const float d2 = dist2(qx0 - v4[u].x, qy0 - v4[u].y, qz0 - v4[u].z);
-                            if (d2 < bd) { bd = d2; bj = c + u; }
+                    for (int j = 0; j < 8; ++j) {
+                        const int e = (j & 1) ? (int)(w[j >> 1] >> 16) : (int)(w[j >> 1] & 0xFFFFu);
+                        room |= (fill[e] < rho ? 1u : 0u) << j;
+                    }
+                    const int base = idx & ~7, lim = nopen - base;   // entries before idx are behind, those from nopen on are padding
+                    room &= 0xFFu << (idx & 7);
+                    if (lim < 8) room &= (1u << lim) - 1u;
+                    if (room) {
+                        const int j = __builtin_ctz(room);
+                        idx = base + j;
+                        c = chunk_entry(cur, j);
+                        contend = true;
+                        break;
+                    }
+                    idx = base + 8;
+                    if (idx < nopen) {
+                        const int k = idx >> 3;
+                        if (k < have) {
+                            cur = ring_mine[(size_t)(k & 3) * ring_rows];
+                        } else {
+                            cur = mine[k];
+                            have = k + 1;   // the ring is skipped over: it restarts behind this chunk
                         }
                     }
-                    for (; c < O; ++c) {
-                        const float4 v = o4[c];
-                        const float d2 = dist2(qx0 - v.x, qy0 - v.y, qz0 - v.z);
-                        if (d2 < bd) { bd = d2; bj = c; }
-                    }
-                    mybest = open_list[bj];
                 }
-                const unsigned long long m = match_key(mybest, tl, keybits);
-                const int rank = __popcll(m & lt);
-                const int room = tl ? rho - fill[mybest] : 0;
-                const bool join = tl && rank < room;
-                if (join) {
-                    tsub = mybest;
-                    tslot = fill[mybest] + rank;
+            }
+            {
+                const bool ask = left && have < nchunks && have <= (idx >> 3) + 3;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (ask && (have & 3) == q)
+                        lds_dma16(mine + have, ring_lds + (uint32_t)((q * ring_rows + wave_u * 64) * 16));
                 }
-                __threadfence_block();   // every lane has read the fill levels
-                if (tl && rank == 0) fill[mybest] += min((int)__popcll(m), room);
-                __threadfence_block();
-                tl = tl && !join;
+                if (ask) ++have;
             }
-            if (lane < L) {
-                res_sub[lane] = (uint16_t)tsub;
-                res_slot[lane] = (uint16_t)tslot;
+            for (;;) {   // passes of one round: the lowest contender of every sub-bucket joins, while there is room
+                if (contend) atomicMin(&win[par * kp + c], tid);
+                lds_barrier();
+                if (contend && win[par * kp + c] == tid) {
+                    const int f = fill[c];
+                    rsub[tid] = (uint16_t)c;
+                    rslot[tid] = (uint16_t)f;
+                    fill[c] = f + 1;
+                    left = false;
+                    contend = false;
+                    atomicSub(&rows_left, 1);
+                    win[par * kp + c] = 0x7FFFFFFF;   // next written by a pass of this parity, two barriers from here
+                }
+                if (tid == 0) more[par ^ 1] = 0;
+                lds_barrier();
+                if (rho <= 2) break;   // a sub-bucket holds a row, so it has room for one at most
+                contend = contend && fill[c] < rho;
+                if (contend) more[par] = 1;
+                lds_barrier();
+                const int again = more[par];
+                par ^= 1;
+                if (!again) break;
             }
+            if (rho <= 2) par ^= 1;
+            if (rows_left <= 0) break;
         }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no load into the ring is left in flight
         __syncthreads();
-        if (left) {
-            sub = res_sub[lpos];
-            slot = res_slot[lpos];
+        if (left0 && rsub[lpos] != 0xFFFF) {
+            sub = rsub[lpos];
+            slot = rslot[lpos];
         }
     }
 
@@ -502,12 +614,14 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
         dst[1] = sy / c;
         dst[2] = sz / c;
     }
+  }   // next tile
 }
 
-size_t pool_lds_bytes(int kp)
+size_t pool_lds_bytes(int kp, int ring_rows)
 {
-    return (size_t)3 * PT * 4 + (size_t)4 * kp * 4 + (size_t)kp * 4 + (size_t)PW * kp * 2 + (size_t)4 * kp * 2 +
-           (size_t)(PT + POOL_MAX_RHO) * 2 + (size_t)3 * PT * 2;
+    const size_t wcnt = (size_t)PW * kp * 2, ring = (size_t)64 * ring_rows;
+    return (size_t)3 * PT * 4 + (size_t)4 * kp * 4 + (size_t)3 * kp * 4 + (size_t)4 * kp * 2 + (size_t)(PT + POOL_MAX_RHO) * 2 +
+           (size_t)2 * PT * 2 + (wcnt > ring ? wcnt : ring);
 }
 
 }  // namespace
@@ -516,12 +630,12 @@ hipError_t pool_launch(const PoolArgs& a, hipStream_t stream)
 {
     k_pool_meta<<<1, 1024, 0, stream>>>(a);
     if (a.n == 0) return hipGetLastError();
-    const size_t lds = pool_lds_bytes(a.kp);
+    const size_t lds = pool_lds_bytes(a.kp, a.ring_rows);
     if (lds > 60000) {
         const hipError_t e = hipFuncSetAttribute((const void*)k_pool, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    k_pool<<<a.n_tiles_ub, PT, lds, stream>>>(a);
+    k_pool<<<a.n_slots, PT, lds, stream>>>(a);
     return hipGetLastError();
 }
 
