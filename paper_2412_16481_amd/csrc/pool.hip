@@ -171,10 +171,12 @@ __device__ __forceinline__ unsigned int dpp_mov(unsigned int old, unsigned int x
 template <int D>
 __device__ __forceinline__ unsigned int lane_xor(unsigned int x, int lane)
 {
-    if (D == 1) return dpp_mov<0xB1, 0xF>(x, x);    // quad_perm [1,0,3,2]
-    if (D == 2) return dpp_mov<0x4E, 0xF>(x, x);    // quad_perm [2,3,0,1]
-    if (D == 4) return dpp_mov<0x124, 0xA>(dpp_mov<0x12C, 0x5>(x, x), x);   // row_ror 12 for lanes 0-3, 8-11; row_ror 4 for the others
-    if (D == 8) return dpp_mov<0x128, 0xF>(x, x);   // row_ror 8
+    // every lane is written, so the moves that cover all banks need no previous value (and no copy to provide one)
+    if (D == 1) return (unsigned int)__builtin_amdgcn_mov_dpp((int)x, 0xB1, 0xF, 0xF, false);    // quad_perm [1,0,3,2]
+    if (D == 2) return (unsigned int)__builtin_amdgcn_mov_dpp((int)x, 0x4E, 0xF, 0xF, false);    // quad_perm [2,3,0,1]
+    if (D == 4)   // row_ror 12 for lanes 0-3 and 8-11 of a row, row_ror 4 for the others
+        return dpp_mov<0x124, 0xA>((unsigned int)__builtin_amdgcn_mov_dpp((int)x, 0x12C, 0xF, 0xF, false), x);
+    if (D == 8) return (unsigned int)__builtin_amdgcn_mov_dpp((int)x, 0x128, 0xF, 0xF, false);   // row_ror 8
     if (D == 16) {
         const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
         return (lane & 16) ? r[0] : r[1];
@@ -288,6 +290,45 @@ __device__ __forceinline__ int chunk_entry(const uint4& c, int i)
     return (int)((half >> ((i & 3) << 4)) & 0xFFFFull);
 }
 
+// The passes of one round, by all threads of the workgroup: thread `tid` speaks for a row that contends for
+// sub-bucket c (or for none). The lowest contender of every sub-bucket joins; with room for more than one the
+// others try again, in row order, while there is room. win [2][kp] holds the lowest contender per sub-bucket,
+// alternating by pass (par); a winner clears its entry, which is next written two barriers later. Returns whether
+// this thread's row joined; its sub-bucket and slot are then in rsub / rslot [tid].
+__device__ __forceinline__ bool join_passes(bool contend, int c, int tid, int rho, int kp, int* win, int* fill, uint16_t* rsub,
+                                            uint16_t* rslot, int* rows_left, int* more, int& par, bool sent = false)
+{
+    bool joined = false;
+    for (;;) {
+        if (contend && !sent) atomicMin(&win[par * kp + c], tid);   // sent: the caller has done this for the first pass
+        sent = false;
+        lds_barrier();
+        if (contend && win[par * kp + c] == tid) {
+            const int f = fill[c];
+            rsub[tid] = (uint16_t)c;
+            rslot[tid] = (uint16_t)f;
+            fill[c] = f + 1;
+            joined = true;
+            contend = false;
+            atomicSub(rows_left, 1);
+            win[par * kp + c] = 0x7FFFFFFF;
+        }
+        if (tid == 0) more[par ^ 1] = 0;
+        lds_barrier();
+        if (rho <= 2) {   // a sub-bucket holds a row, so it has room for one at most
+            par ^= 1;
+            break;
+        }
+        contend = contend && fill[c] < rho;
+        if (contend) more[par] = 1;
+        lds_barrier();
+        const int again = more[par];
+        par ^= 1;
+        if (!again) break;
+    }
+    return joined;
+}
+
 // dynamic LDS, kp = a.kp: px,py,pz [PT] floats | o4 [kp] float4 (x, y, z, -) | fill [kp] ints | win [2][kp] ints |
 // open_list, id_of_hash, first_idx, ktot [kp] u16 each | members [PT + POOL_MAX_RHO] u16 | rsub, rslot [PT] u16 |
 // wcnt [PW][kp] u16, later reused as ring [4][ring_rows] of 16 bytes (the next 32 choices of every row left)
@@ -356,7 +397,6 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
         win[kp + k] = 0x7FFFFFFF;
     }
     if (tid == 0) { more[0] = 0; more[1] = 0; }
-    rsub[tid] = (uint16_t)0xFFFF;
     __syncthreads();
     {
         uint32_t o[3] = {act ? f2ord(x) : 0xFFFFFFFFu, act ? f2ord(y) : 0xFFFFFFFFu, act ? f2ord(z) : 0xFFFFFFFFu};
@@ -420,31 +460,94 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
         fill[sub] = 1;
         first_idx[sub] = (uint16_t)tid;
     }
-    const bool left0 = act && sub < 0;
     // ---- rounds: every row still left picks the open sub-bucket whose first row is nearest (state at the start of
-    //      the round); the contenders of a sub-bucket join in row order while it has room. A sub-bucket never
-    //      reopens and its first row never changes, so the choices of a row over all rounds are one fixed sequence:
-    //      the sub-buckets open now, by (distance, id), of which the row takes the first that still has room. The
-    //      sequences are written once (a wave sorts one row's candidates at a time); a round is then a step along
-    //      them.
+    //      the round); the contenders of a sub-bucket join in row order while it has room.
+    //      The first rounds search: every row left scans the open sub-buckets. That pays while a round places many
+    //      rows (isolated rows find a sub-bucket of their own at once). What remains are the rows of dense clusters,
+    //      which share their nearest sub-buckets and get one of them per round. For them the search is taken out
+    //      of the rounds: a sub-bucket never reopens and its first row never changes, so the choices of a row over
+    //      all rounds are one fixed sequence: the sub-buckets open now, by (distance, id), of which the row takes
+    //      the first that still has room. The sequences are written once (a wave sorts one row's candidates at a
+    //      time); a round is then a step along them.
     uint16_t* left_list = members;   // [PT] thread ids of the rows still left, in row order (members is filled last)
-    __syncthreads();                 // the fill levels written above are in place
-    int lpos, nleft, nopen;
-    {
-        const bool open = tid < M && fill[tid] < rho;
-        int tot;
-        const int pre = block_excl_scan((left0 ? 1 : 0) | (open ? 0x10000 : 0), &tot, lds);
-        lpos = pre & 0xFFFF;
-        nleft = tot & 0xFFFF;
-        nopen = tot >> 16;
-        if (left0) left_list[lpos] = (uint16_t)tid;
-        if (open) {
-            const int f = first_idx[tid], opos = pre >> 16;
-            open_list[opos] = (uint16_t)tid;
-            o4[opos] = make_float4(px[f], py[f], pz[f], 0.f);
+    uint16_t* pick = reinterpret_cast<uint16_t*>(ring);   // [PT] choices of a searched round (the ring is filled after them)
+    bool left = act && sub < 0;
+    int lpos = 0, nleft = 0, nopen = 0, par = 0;
+    for (int searched = 0, joined_last = 0, nleft_before = 0;; ++searched) {
+        // one scan builds both lists: the rows still left (low half) and the sub-buckets with room (high half)
+        __syncthreads();   // the fill levels written by the steps above / the last round are in place
+        {
+            const bool open = tid < M && fill[tid] < rho;
+            int tot;
+            const int pre = block_excl_scan((left ? 1 : 0) | (open ? 0x10000 : 0), &tot, lds);
+            lpos = pre & 0xFFFF;
+            nleft = tot & 0xFFFF;
+            nopen = tot >> 16;
+            if (left) left_list[lpos] = (uint16_t)tid;
+            if (open) {
+                const int f = first_idx[tid], opos = pre >> 16;
+                open_list[opos] = (uint16_t)tid;
+                o4[opos] = make_float4(px[f], py[f], pz[f], 0.f);
+            }
+            if (tid == 0) rows_left = nleft;
+            rsub[tid] = (uint16_t)0xFFFF;
+            __syncthreads();
         }
-        if (tid == 0) rows_left = nleft;
+        // a searched round costs about nleft * nopen / 6 vector instructions, a sorted list about 2000 per row
+        if (nleft == 0 || nopen == 0 || (searched > 0 && (searched >= 8 || joined_last * 16 < nleft_before))) break;
+        // the rows left are spread over all threads: g neighbouring lanes share one row's search
+        int g = 1;
+        while (g < 64 && nleft * g * 2 <= PT) g *= 2;
+        const int p = tid / g, part = tid - p * g;
+        float bd = __builtin_inff();
+        int bi = 0x7FFFFFFF;
+        if (p < nleft) {
+            const int id = left_list[p];
+            const float qx = px[id], qy = py[id], qz = pz[id];
+            // Lane `part` of the row's g lanes takes a contiguous range of the open list, in ascending order: the first
+            // candidate unconditionally, a later one only if strictly nearer (a tie keeps the lower sub-bucket id). Four
+            // candidates per trip, their reads issued together.
+            const int chunk = (nopen + g - 1) / g;
+            int c = part * chunk;
+            const int cend = min(c + chunk, nopen);
+            if (c < cend) {
+                const float4 o = o4[c];
+                bd = dist2(qx - o.x, qy - o.y, qz - o.z);
+                bi = c;
+                ++c;
+                for (; c + 3 < cend; c += 4) {
+                    float4 v4[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) v4[u] = o4[c + u];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const float d2 = dist2(qx - v4[u].x, qy - v4[u].y, qz - v4[u].z);
+                        if (d2 < bd) { bd = d2; bi = c + u; }
+                    }
+                }
+                for (; c < cend; ++c) {
+                    const float4 v = o4[c];
+                    const float d2 = dist2(qx - v.x, qy - v.y, qz - v.z);
+                    if (d2 < bd) { bd = d2; bi = c; }
+                }
+            }
+        }
+        for (int d = g >> 1; d >= 1; d >>= 1) {   // smallest distance, the lower list position on a tie
+            const float od = __shfl_xor(bd, d, 64);
+            const int oi = __shfl_xor(bi, d, 64);
+            if (oi != 0x7FFFFFFF && (bi == 0x7FFFFFFF || od < bd || (od == bd && oi < bi))) { bd = od; bi = oi; }
+        }
+        if (p < nleft && part == 0) pick[p] = open_list[min(bi, nopen - 1)];
         __syncthreads();
+        // thread t now speaks for the t-th row left: row order is kept
+        join_passes(tid < nleft, tid < nleft ? (int)pick[tid] : 0, tid, rho, kp, win, fill, rsub, rslot, &rows_left, more, par);
+        if (left && rsub[lpos] != 0xFFFF) {
+            sub = rsub[lpos];
+            slot = rslot[lpos];
+            left = false;
+        }
+        joined_last = nleft - rows_left;
+        nleft_before = nleft;
     }
     const int pitch = (nopen + 7) & ~7;
     if (nleft > 0 && nopen > 0 && nleft <= ring_rows && (long long)nleft * pitch <= (long long)a.list_cap) {
@@ -461,19 +564,19 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
         // the thread asks for chunk k + 3 by a global->LDS load into the ring slot chunk k - 1 has left; such loads
         // are waited for at the start of the next round, so a chunk asked for in an earlier round is there. A row
         // that runs ahead of its requests (many closed sub-buckets in a row) reads its list from memory directly.
-        bool left = tid < nleft;
+        bool walking = tid < nleft;
         const uint4* mine = reinterpret_cast<const uint4*>(my_lists + (size_t)tid * pitch);
         const int nchunks = pitch >> 3;
         const int wave_u = __builtin_amdgcn_readfirstlane(tid >> 6);
         const uint4* ring_mine = reinterpret_cast<const uint4*>(ring) + tid;   // + q * ring_rows
         uint4 cur = make_uint4(0, 0, 0, 0);
-        if (left) cur = ring_mine[0];
+        if (walking) cur = ring_mine[0];
         int have = min(4, nchunks);   // chunks 0 .. have - 1 have been asked for
-        int idx = 0, c = 0, par = 0;
+        int idx = 0, c = 0;
         for (int round = 0; round <= PT; ++round) {   // every round places at least one row; the bound is a safeguard
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the chunks asked for in the round before have arrived
             bool contend = false;
-            if (left) {
+            if (walking) {
                 for (;;) {   // the first sub-bucket of the sequence that still has room
                     if (idx >= nopen) break;
                     // all eight entries of the chunk are looked up together (their reads overlap, no branch per entry)
@@ -506,8 +609,9 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
                     }
                 }
             }
+            if (contend) atomicMin(&win[par * kp + c], tid);   // first step of the passes, under way during the requests below
             {
-                const bool ask = left && have < nchunks && have <= (idx >> 3) + 3;
+                const bool ask = walking && have < nchunks && have <= (idx >> 3) + 3;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     if (ask && (have & 3) == q)
@@ -515,35 +619,12 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
                 }
                 if (ask) ++have;
             }
-            for (;;) {   // passes of one round: the lowest contender of every sub-bucket joins, while there is room
-                if (contend) atomicMin(&win[par * kp + c], tid);
-                lds_barrier();
-                if (contend && win[par * kp + c] == tid) {
-                    const int f = fill[c];
-                    rsub[tid] = (uint16_t)c;
-                    rslot[tid] = (uint16_t)f;
-                    fill[c] = f + 1;
-                    left = false;
-                    contend = false;
-                    atomicSub(&rows_left, 1);
-                    win[par * kp + c] = 0x7FFFFFFF;   // next written by a pass of this parity, two barriers from here
-                }
-                if (tid == 0) more[par ^ 1] = 0;
-                lds_barrier();
-                if (rho <= 2) break;   // a sub-bucket holds a row, so it has room for one at most
-                contend = contend && fill[c] < rho;
-                if (contend) more[par] = 1;
-                lds_barrier();
-                const int again = more[par];
-                par ^= 1;
-                if (!again) break;
-            }
-            if (rho <= 2) par ^= 1;
+            if (join_passes(contend, c, tid, rho, kp, win, fill, rsub, rslot, &rows_left, more, par, true)) walking = false;
             if (rows_left <= 0) break;
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no load into the ring is left in flight
         __syncthreads();
-        if (left0 && rsub[lpos] != 0xFFFF) {
+        if (left && rsub[lpos] != 0xFFFF) {
             sub = rsub[lpos];
             slot = rslot[lpos];
         }
