@@ -224,10 +224,88 @@ __device__ __forceinline__ void wave_sort_keys(unsigned long long (&key)[NPL], i
     if constexpr (K < 64 * NPL) wave_sort_keys<NPL, K * 2>(key, lane);
 }
 
+// The same network on 32-bit keys, at less than half the instructions: a step is a minimum and a maximum. Runs that
+// are to end up descending are sorted ascending on complemented keys instead (the lanes of such a run flip their keys
+// when the phase begins), so no step depends on a direction except through the constant choice of the lower lane.
+template <int NPL, int K, int J>
+__device__ __forceinline__ void sort32_step(unsigned int (&key)[NPL], int lane)
+{
+    if constexpr (J >= NPL) {
+        constexpr int LJ = J / NPL;
+        const bool lower = (lane & LJ) == 0;
+#pragma unroll
+        for (int r = 0; r < NPL; ++r) {
+            const unsigned int other = lane_xor<LJ>(key[r], lane);
+            const unsigned int lo = min(key[r], other), hi = max(key[r], other);
+            key[r] = lower ? lo : hi;
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < NPL; ++r) {
+            if (r & J) continue;
+            const bool up = K < NPL ? (r & K) == 0 : true;
+            const unsigned int lo = min(key[r], key[r | J]), hi = max(key[r], key[r | J]);
+            key[r] = up ? lo : hi;
+            key[r | J] = up ? hi : lo;
+        }
+    }
+    if constexpr (J > 1) sort32_step<NPL, K, J / 2>(key, lane);
+}
+template <int NPL, int K = 2>
+__device__ __forceinline__ void wave_sort32(unsigned int (&key)[NPL], int lane)
+{
+    if constexpr (K >= NPL) {
+        const bool up_now = K >= 64 * NPL ? true : (lane & (K / NPL)) == 0;
+        const bool up_before = K / 2 >= NPL ? (lane & (K / 2 / NPL)) == 0 : true;
+        const unsigned int flip = up_now != up_before ? 0xFFFFFFFFu : 0u;
+#pragma unroll
+        for (int r = 0; r < NPL; ++r) key[r] ^= flip;
+    }
+    sort32_step<NPL, K, K / 2>(key, lane);
+    if constexpr (K < 64 * NPL) wave_sort32<NPL, K * 2>(key, lane);
+}
+
+// Odd-even transposition sweeps over the wave's 64 * NPL keys (element lane * NPL + r) until a sweep swaps nothing;
+// false when `sweeps` sweeps did not suffice. For sequences that are sorted except inside short runs.
+template <int NPL>
+__device__ __forceinline__ bool settle_order(unsigned long long (&key)[NPL], int lane, int sweeps)
+{
+    for (int s = 0; s < sweeps; ++s) {
+        bool moved = false;
+#pragma unroll
+        for (int r0 = 0; r0 < 2; ++r0) {
+#pragma unroll
+            for (int r = r0; r + 1 < NPL; r += 2) {
+                const unsigned long long x = key[r], y = key[r + 1];
+                const bool swap = x > y;
+                key[r] = swap ? y : x;
+                key[r + 1] = swap ? x : y;
+                moved |= swap;
+            }
+        }
+        // the pair that straddles two lanes: this lane's last key and the next lane's first
+        const unsigned long long last = key[NPL - 1], first = key[0];
+        const unsigned long long next_first =
+            ((unsigned long long)(unsigned int)__shfl_down((int)(unsigned int)(first >> 32), 1, 64) << 32) | (unsigned int)__shfl_down((int)(unsigned int)first, 1, 64);
+        const unsigned long long prev_last =
+            ((unsigned long long)(unsigned int)__shfl_up((int)(unsigned int)(last >> 32), 1, 64) << 32) | (unsigned int)__shfl_up((int)(unsigned int)last, 1, 64);
+        const bool give = lane < 63 && last > next_first, take = lane > 0 && prev_last > first;
+        if (give) key[NPL - 1] = next_first;
+        if (take) key[0] = prev_last;
+        moved |= give | take;
+        if (__builtin_amdgcn_ballot_w64(moved) == 0ull) return true;
+    }
+    return false;
+}
+
 // One wave writes, for each of the rows left it is given (every PW-th), the ids of the open sub-buckets in the
 // order in which the row would choose them: increasing squared distance to the sub-bucket's first row, the lower id
-// first on a tie. The key is (bits of the distance, id): a squared distance is a non-negative binary32 number, whose
-// bit patterns are ordered like the numbers. `list` rows have `pitch` entries (a multiple of 8, >= nopen).
+// first on a tie, i.e. increasing (bits of the distance, position in the open list): a squared distance is a
+// non-negative binary32 number, whose bit patterns are ordered like the numbers. The sort runs on 32-bit keys (the
+// upper 23 bits of the distance's pattern, 9 bits of position: at most 512 sub-buckets are open when rows are
+// left); that orders all candidates except those whose distances agree in the bits kept, which the full 64-bit keys
+// then settle among neighbours (if that takes long, the full keys are sorted outright). `list` rows have `pitch`
+// entries (a multiple of 8, >= nopen).
 template <int NPL>
 __device__ __forceinline__ void sort_choices(int nleft, int nopen, int pitch, const uint16_t* left_list, const float* px,
                                              const float* py, const float* pz, const float4* o4, const uint16_t* open_list,
@@ -237,18 +315,27 @@ __device__ __forceinline__ void sort_choices(int nleft, int nopen, int pitch, co
     for (int p = wave; p < nleft; p += PW) {
         const int id = left_list[p];
         const float qx = px[id], qy = py[id], qz = pz[id];
-        unsigned long long key[NPL];
+        unsigned int k32[NPL];
 #pragma unroll
         for (int r = 0; r < NPL; ++r) {   // the candidates' positions are read again for every row: registers are scarce
             const int e = lane * NPL + r;
             const float4 o = o4[min(e, nopen - 1)];
             const float d2 = dist2(qx - o.x, qy - o.y, qz - o.z);
-            key[r] = e < nopen ? ((unsigned long long)__float_as_uint(d2) << 32) | open_list[e] : ~0ull;
+            k32[r] = e < nopen ? ((__float_as_uint(d2) >> 8) << 9) | (unsigned int)e : 0xFFFFFFFFu;
         }
-        wave_sort_keys<NPL>(key, lane);
+        wave_sort32<NPL>(k32, lane);
+        unsigned long long key[NPL];
+#pragma unroll
+        for (int r = 0; r < NPL; ++r) {   // the full key of the candidate now at this place
+            const int e = min((int)(k32[r] & 511u), nopen - 1);
+            const float4 o = o4[e];
+            const float d2 = dist2(qx - o.x, qy - o.y, qz - o.z);
+            key[r] = k32[r] != 0xFFFFFFFFu ? ((unsigned long long)__float_as_uint(d2) << 32) | (unsigned int)e : ~0ull;
+        }
+        if (!settle_order<NPL>(key, lane, 16)) wave_sort_keys<NPL>(key, lane);
         unsigned int sid[NPL];   // padding entries (beyond nopen) become id 0: never chosen, but a valid index
 #pragma unroll
-        for (int r = 0; r < NPL; ++r) sid[r] = key[r] == ~0ull ? 0u : (unsigned int)key[r] & 0xFFFFu;
+        for (int r = 0; r < NPL; ++r) sid[r] = key[r] == ~0ull ? 0u : (unsigned int)open_list[(unsigned int)key[r] & 511u];
         if (lane * NPL < 32) {   // the first four chunks of eight also go to the row's ring in LDS (chunk, row, 16 bytes)
             unsigned int* dst = reinterpret_cast<unsigned int*>(ring + ((size_t)((lane * NPL) >> 3) * ring_rows + p) * 16 + ((lane * NPL) & 7) * 2);
 #pragma unroll

@@ -1041,6 +1041,29 @@ def test_pool_near_ties_on_a_lattice():
         assert ref["step_of"].max() >= 3
 
 
+@pytest.mark.parametrize("spread", [0.0, 1e-7, 3e-6, 1e-4, 3e-3])
+def test_pool_candidates_at_nearly_equal_distances(spread):
+    """Many rows at one point, the centre of a shell of points: when these rows run out of sub-buckets of
+    their own, every sub-bucket on the shell is a candidate at almost the same distance (relative differences of
+    `spread`: exactly equal, in the last bits of binary32, in the bits a shortened sort key drops, and well apart).
+    The order of a row's choices, and with it every later round, hangs on the full (distance, id) comparison."""
+    rng = np.random.default_rng(46)
+    for tile_rows, rho in ((1024, 2), (1024, 3), (600, 2)):
+        n = 3 * tile_rows + 17
+        c = np.zeros((n, 3), np.float32)
+        for t0 in range(0, n, tile_rows):
+            m = min(tile_rows, n - t0)
+            shell = (3 * m) // 5   # the shell's rows come first and found the sub-buckets; the cluster's rows are left over
+            u = rng.normal(size=(shell, 3))
+            u /= np.linalg.norm(u, axis=1, keepdims=True)
+            radius = 3.0 * (1.0 + spread * rng.random((shell, 1)))
+            pts = np.concatenate([u * radius, np.zeros((m - shell, 3))])   # the cluster: one point, many times
+            c[t0:t0 + m] = (pts + np.array([7.0, -2.0, 1.5])).astype(np.float32)
+        feat = wl.f32_to_bf16_bits(rng.standard_normal((n, 16)).astype(np.float32))
+        ref = check_pool(c, None, feat, None, tile_rows, rho, 0.2, "zorder_div", "mean")
+        assert ref["step_of"].max() >= 100   # the cluster's rows take the shell's sub-buckets one round at a time
+
+
 def test_pool_empty_input_and_bad_offsets():
     z = np.zeros((0, 3), np.float32)
     got = f3d.inbucket_pool(dev(z), None, dev(np.zeros((0, 8), np.uint16), torch.bfloat16), None, 1024, 2, 0.1)
