@@ -381,17 +381,26 @@ __device__ __forceinline__ int chunk_entry(const uint4& c, int i)
 // sub-bucket c (or for none). The lowest contender of every sub-bucket joins; with room for more than one the
 // others try again, in row order, while there is room. win [2][kp] holds the lowest contender per sub-bucket,
 // alternating by pass (par); a winner clears its entry, which is next written two barriers later. Returns whether
-// this thread's row joined; its sub-bucket and slot are then in rsub / rslot [tid].
+// this thread's row joined; its sub-bucket and slot are then in rsub / rslot [tid]. `probe`, when given, is a word of
+// LDS read right after the first barrier (with the other reads of that moment) into *probed.
 __device__ __forceinline__ bool join_passes(bool contend, int c, int tid, int rho, int kp, int* win, int* fill, uint16_t* rsub,
-                                            uint16_t* rslot, int* rows_left, int* more, int& par, bool sent = false)
+                                            uint16_t* rslot, int* rows_left, int* more, int& par, bool sent = false,
+                                            const int* probe = nullptr, int* probed = nullptr)
 {
     bool joined = false;
     for (;;) {
         if (contend && !sent) atomicMin(&win[par * kp + c], tid);   // sent: the caller has done this for the first pass
         sent = false;
         lds_barrier();
-        if (contend && win[par * kp + c] == tid) {
-            const int f = fill[c];
+        // the fill level is read beside the winner, not after it: one LDS round trip instead of two
+        const int w = contend ? win[par * kp + c] : -1;
+        const int f = contend ? fill[c] : 0;
+        if (probe) {
+            *probed = *probe;
+            probe = nullptr;
+        }
+        asm volatile("" ::"v"(f));
+        if (contend && w == tid) {
             rsub[tid] = (uint16_t)c;
             rslot[tid] = (uint16_t)f;
             fill[c] = f + 1;
@@ -431,6 +440,7 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
     __shared__ int next_tile;
     __shared__ int rows_left;
     __shared__ int more[2];
+    __shared__ int any[2];
     const int rho = a.rho, kp = a.kp;
     const int tid = threadIdx.x, lane = tid & 63;
     float* px = reinterpret_cast<float*>(smem);
@@ -483,7 +493,7 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
         win[k] = 0x7FFFFFFF;
         win[kp + k] = 0x7FFFFFFF;
     }
-    if (tid == 0) { more[0] = 0; more[1] = 0; }
+    if (tid == 0) { more[0] = 0; more[1] = 0; any[0] = 0; any[1] = 0; }
     __syncthreads();
     {
         uint32_t o[3] = {act ? f2ord(x) : 0xFFFFFFFFu, act ? f2ord(y) : 0xFFFFFFFFu, act ? f2ord(z) : 0xFFFFFFFFu};
@@ -659,10 +669,11 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
         uint4 cur = make_uint4(0, 0, 0, 0);
         if (walking) cur = ring_mine[0];
         int have = min(4, nchunks);   // chunks 0 .. have - 1 have been asked for
-        int idx = 0, c = 0;
-        for (int round = 0; round <= PT; ++round) {   // every round places at least one row; the bound is a safeguard
+        int idx = 0, c = 0, rpar = 0;
+        for (int round = 0; round <= PT + 1; ++round) {   // every round places at least one row; the bound is a safeguard
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the chunks asked for in the round before have arrived
             bool contend = false;
+            if (tid == 0) any[rpar ^ 1] = 0;
             if (walking) {
                 for (;;) {   // the first sub-bucket of the sequence that still has room
                     if (idx >= nopen) break;
@@ -671,8 +682,8 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
                     unsigned int room = 0;
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
-                        const int e = (j & 1) ? (int)(w[j >> 1] >> 16) : (int)(w[j >> 1] & 0xFFFFu);
-                        room |= (fill[e] < rho ? 1u : 0u) << j;
+                        const unsigned int eo = (j & 1) ? (w[j >> 1] >> 14) & ~3u : (w[j >> 1] << 2) & 0x3FFFCu;   // 4 * id
+                        room |= (*reinterpret_cast<const int*>(reinterpret_cast<const char*>(fill) + eo) < rho ? 1u : 0u) << j;
                     }
                     const int base = idx & ~7, lim = nopen - base;   // entries before idx are behind, those from nopen on are padding
                     room &= 0xFFu << (idx & 7);
@@ -696,7 +707,10 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
                     }
                 }
             }
-            if (contend) atomicMin(&win[par * kp + c], tid);   // first step of the passes, under way during the requests below
+            if (contend) {   // first step of the passes, under way during the requests below
+                atomicMin(&win[par * kp + c], tid);
+                any[rpar] = 1;
+            }
             {
                 const bool ask = walking && have < nchunks && have <= (idx >> 3) + 3;
 #pragma unroll
@@ -706,8 +720,10 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
                 }
                 if (ask) ++have;
             }
-            if (join_passes(contend, c, tid, rho, kp, win, fill, rsub, rslot, &rows_left, more, par, true)) walking = false;
-            if (rows_left <= 0) break;
+            int seen = 0;   // did any row contend in this round? (the same answer for every thread)
+            if (join_passes(contend, c, tid, rho, kp, win, fill, rsub, rslot, &rows_left, more, par, true, &any[rpar], &seen)) walking = false;
+            rpar ^= 1;
+            if (!seen) break;
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no load into the ring is left in flight
         __syncthreads();
