@@ -477,7 +477,13 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
         scores(sa, kf1, 0);
         if (QT == 1) read_k(kf1, 0, 1);    // a stage always holds four tiles of (clamped, finite) rows
         int bufi = 0;
-        for (int st = 0; st + 1 < nst; ++st) {          // stages with a successor: no tile is masked, every tile has a next one
+        // A scope of whole stages (every scope of full buckets) runs its last stage through the same straight code:
+        // the score tile computed "ahead" of the very last one reads a buffer that holds no stage and is never used.
+        // The general version of the last stage decides per tile at run time whether there is a next one; the joins
+        // of its paths cost more register moves than a tile's own arithmetic.
+        const bool whole = (ng & (AKT - 1)) == 0;
+        const int nfast = whole ? nst : nst - 1;
+        for (int st = 0; st < nfast; ++st) {            // no tile is masked, every tile has a next one (see above for the last)
             const int bufn = bufi + 1 == NBUF ? 0 : bufi + 1;
             const uint32_t kb = bufi * L::KBUF, vb = bufi * L::VBUF, kbn = bufn * L::KBUF;
             const int k0 = st * AKT;
@@ -499,7 +505,7 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
             }
             bufi = bufn;
         }
-        {                                               // the last stage: 1..4 tiles, the last one possibly ragged
+        if (!whole) {                                   // the last stage: 1..4 tiles, the last one possibly ragged
             const uint32_t kb = bufi * L::KBUF, vb = bufi * L::VBUF;
             const int k0 = (nst - 1) * AKT;
             const int ntl = ntile - (nst - 1) * 4;
