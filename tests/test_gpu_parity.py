@@ -1000,6 +1000,22 @@ def test_pool_matches_oracle_on_the_indoor_layout(hash, rho, op):
     check_pool(w.coords, perm, feat, w.batch_offsets, 1024, rho, 0.1, hash, op)
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("rho,op", [(2, "mean"), (5, "max")])
+def test_pool_matches_oracle_on_the_largest_lidar_layout(rho, op):
+    """893 tiles of 1024 rows: more tiles than resident workgroups, so every workgroup takes several tiles in turn and
+    reuses its LDS and its list area; tiles of this layout leave about 480 rows to the rounds and need up to 400 of
+    them, one row joining per round (the long walk along the sorted lists, chunk after chunk through the ring)."""
+    w = wl.make_workload("lidar8")
+    bk = run_bucketize(w.coords, w.batch_offsets, w.voxel_size, w.bucket_cap, max_scan_points=int(np.diff(w.batch_offsets).max()))
+    perm = bk.perm.cpu().numpy()
+    rng = np.random.default_rng(47)
+    feat = wl.f32_to_bf16_bits(rng.standard_normal((w.n, 16)).astype(np.float32))
+    ref = check_pool(w.coords, perm, feat, w.batch_offsets, 1024, rho, 0.1, "zorder_div", op)
+    if rho == 2:
+        assert ref["step_of"].max() >= 300
+
+
 def test_pool_on_scans_with_ragged_tiles_and_bucket_major_coordinates():
     rng = np.random.default_rng(41)
     sizes = [1, 1023, 1024, 1025, 0, 3000, 77, 0, 5]
