@@ -600,7 +600,6 @@ int f3d_inbucket_pool(const float* coords, const int32_t* perm, const void* feat
     a.lists = (uint16_t*)((char*)a.tile_counter + 256);
     a.list_cap = f3d::pool_list_entries(tile);
     a.n_slots = a.n_tiles_ub < f3d::POOL_MAX_SLOTS ? a.n_tiles_ub : f3d::POOL_MAX_SLOTS;
-    a.ring_rows = (tile - (tile + rho - 1) / rho + 63) / 64 * 64;
     (void)hipGetLastError();
     const hipError_t e = f3d::pool_launch(a, (hipStream_t)stream);
     return e == hipSuccess ? F3D_OK : hip_fail(e);

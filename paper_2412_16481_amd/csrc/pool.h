@@ -37,7 +37,6 @@ struct PoolArgs {
     uint16_t* lists;               // workspace: [n_slots][list_cap] sorted choices of the rows left, per workgroup
     size_t list_cap;
     int n_slots;                   // workgroups of the pooling kernel
-    int ring_rows;                 // most rows left after the first two steps, tile - ceil(tile / rho), rounded up to 64
 };
 
 hipError_t pool_launch(const PoolArgs& a, hipStream_t stream);

@@ -309,7 +309,7 @@ __device__ __forceinline__ bool settle_order(unsigned long long (&key)[NPL], int
 template <int NPL>
 __device__ __forceinline__ void sort_choices(int nleft, int nopen, int pitch, const uint16_t* left_list, const float* px,
                                              const float* py, const float* pz, const float4* o4, const uint16_t* open_list,
-                                             uint16_t* list, unsigned char* ring, int ring_rows)
+                                             uint16_t* list)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int p = wave; p < nleft; p += PW) {
@@ -336,11 +336,6 @@ __device__ __forceinline__ void sort_choices(int nleft, int nopen, int pitch, co
         unsigned int sid[NPL];   // padding entries (beyond nopen) become id 0: never chosen, but a valid index
 #pragma unroll
         for (int r = 0; r < NPL; ++r) sid[r] = key[r] == ~0ull ? 0u : (unsigned int)open_list[(unsigned int)key[r] & 511u];
-        if (lane * NPL < 32) {   // the first four chunks of eight also go to the row's ring in LDS (chunk, row, 16 bytes)
-            unsigned int* dst = reinterpret_cast<unsigned int*>(ring + ((size_t)((lane * NPL) >> 3) * ring_rows + p) * 16 + ((lane * NPL) & 7) * 2);
-#pragma unroll
-            for (int r = 0; r < NPL; r += 2) dst[r >> 1] = sid[r] | (sid[r + 1] << 16);
-        }
         if (lane * NPL < pitch) {
             uint16_t* dst = list + (size_t)p * pitch + lane * NPL;
             if (NPL == 8) {
@@ -359,13 +354,6 @@ __device__ __forceinline__ void sort_choices(int nleft, int nopen, int pitch, co
 __device__ __forceinline__ void lds_barrier()
 {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
-// 16 bytes per lane from global memory straight into LDS: lane i's piece lands at byte address lds + 16 i (the
-// hardware adds the lane's offset to the base in M0). Not tracked by the compiler: the caller waits (vmcnt).
-__device__ __forceinline__ void lds_dma16(const void* g, uint32_t lds)
-{
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds), "v"(g) : "memory", "m0");
 }
 
 // entry `i` (0..7) of a chunk of eight 16-bit ids
@@ -427,7 +415,7 @@ __device__ __forceinline__ bool join_passes(bool contend, int c, int tid, int rh
 
 // dynamic LDS, kp = a.kp: px,py,pz [PT] floats | o4 [kp] float4 (x, y, z, -) | fill [kp] ints | win [2][kp] ints |
 // open_list, id_of_hash, first_idx, ktot [kp] u16 each | members [PT + POOL_MAX_RHO] u16 | rsub, rslot [PT] u16 |
-// wcnt [PW][kp] u16, later reused as ring [4][ring_rows] of 16 bytes (the next 32 choices of every row left)
+// wcnt [PW][kp] u16 (at least PT entries: later the choices of a searched round)
 //
 // Workgroups are persistent: each takes tiles from a counter until none is left, and owns one slot of the
 // choice-list area in global memory (its block index).
@@ -457,9 +445,6 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
     uint16_t* rsub = members + PT + POOL_MAX_RHO;    // [PT] sub-bucket the t-th row left joined, and its slot there
     uint16_t* rslot = rsub + PT;
     uint16_t* wcnt = rslot + PT;                        // per-wave counters of the ranking by key (initial sub-buckets only)
-    unsigned char* ring = reinterpret_cast<unsigned char*>(wcnt);
-    const int ring_rows = a.ring_rows;
-    const uint32_t ring_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)ring;   // LDS byte address
     uint16_t* const my_lists = a.lists + (size_t)blockIdx.x * a.list_cap;
 
   for (;;) {
@@ -567,7 +552,7 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
     //      the first that still has room. The sequences are written once (a wave sorts one row's candidates at a
     //      time); a round is then a step along them.
     uint16_t* left_list = members;   // [PT] thread ids of the rows still left, in row order (members is filled last)
-    uint16_t* pick = reinterpret_cast<uint16_t*>(ring);   // [PT] choices of a searched round (the ring is filled after them)
+    uint16_t* pick = wcnt;   // [PT] choices of a searched round (the counters of the ranking are free by then)
     bool left = act && sub < 0;
     int lpos = 0, nleft = 0, nopen = 0, par = 0;
     for (int searched = 0, joined_last = 0, nleft_before = 0;; ++searched) {
@@ -647,31 +632,26 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
         nleft_before = nleft;
     }
     const int pitch = (nopen + 7) & ~7;
-    if (nleft > 0 && nopen > 0 && nleft <= ring_rows && (long long)nleft * pitch <= (long long)a.list_cap) {
+    if (nleft > 0 && nopen > 0 && (long long)nleft * pitch <= (long long)a.list_cap) {
         if (nopen <= 128)
-            sort_choices<2>(nleft, nopen, pitch, left_list, px, py, pz, o4, open_list, my_lists, ring, ring_rows);
+            sort_choices<2>(nleft, nopen, pitch, left_list, px, py, pz, o4, open_list, my_lists);
         else if (nopen <= 256)
-            sort_choices<4>(nleft, nopen, pitch, left_list, px, py, pz, o4, open_list, my_lists, ring, ring_rows);
+            sort_choices<4>(nleft, nopen, pitch, left_list, px, py, pz, o4, open_list, my_lists);
         else
-            sort_choices<8>(nleft, nopen, pitch, left_list, px, py, pz, o4, open_list, my_lists, ring, ring_rows);
+            sort_choices<8>(nleft, nopen, pitch, left_list, px, py, pz, o4, open_list, my_lists);
         __threadfence_block();   // the lists are read by other waves of this workgroup
         __syncthreads();
-        // Thread t now speaks for the t-th row left: row order is kept. It walks its list in chunks of eight entries.
-        // The chunk in use sits in registers; the row's ring in LDS holds it and the three after it. Entering chunk k,
-        // the thread asks for chunk k + 3 by a global->LDS load into the ring slot chunk k - 1 has left; such loads
-        // are waited for at the start of the next round, so a chunk asked for in an earlier round is there. A row
-        // that runs ahead of its requests (many closed sub-buckets in a row) reads its list from memory directly.
+        // Thread t now speaks for the t-th row left: row order is kept. It walks its list in chunks of eight entries
+        // (16 bytes), the chunk in use in registers. The lists were written by this compute unit a moment ago and
+        // come back from its caches; a ring of the next chunks in LDS, refilled by global->LDS loads a round ahead,
+        // measured no faster than reading a chunk when it is entered: the rounds are bound by the number of
+        // instructions a wave issues per round, not by this latency.
         bool walking = tid < nleft;
         const uint4* mine = reinterpret_cast<const uint4*>(my_lists + (size_t)tid * pitch);
-        const int nchunks = pitch >> 3;
-        const int wave_u = __builtin_amdgcn_readfirstlane(tid >> 6);
-        const uint4* ring_mine = reinterpret_cast<const uint4*>(ring) + tid;   // + q * ring_rows
         uint4 cur = make_uint4(0, 0, 0, 0);
-        if (walking) cur = ring_mine[0];
-        int have = min(4, nchunks);   // chunks 0 .. have - 1 have been asked for
+        if (walking) cur = mine[0];
         int idx = 0, c = 0, rpar = 0;
         for (int round = 0; round <= PT + 1; ++round) {   // every round places at least one row; the bound is a safeguard
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the chunks asked for in the round before have arrived
             bool contend = false;
             if (tid == 0) any[rpar ^ 1] = 0;
             if (walking) {
@@ -696,36 +676,18 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
                         break;
                     }
                     idx = base + 8;
-                    if (idx < nopen) {
-                        const int k = idx >> 3;
-                        if (k < have) {
-                            cur = ring_mine[(size_t)(k & 3) * ring_rows];
-                        } else {
-                            cur = mine[k];
-                            have = k + 1;   // the ring is skipped over: it restarts behind this chunk
-                        }
-                    }
+                    if (idx < nopen) cur = mine[idx >> 3];
                 }
             }
-            if (contend) {   // first step of the passes, under way during the requests below
+            if (contend) {   // first step of the passes
                 atomicMin(&win[par * kp + c], tid);
                 any[rpar] = 1;
-            }
-            {
-                const bool ask = walking && have < nchunks && have <= (idx >> 3) + 3;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    if (ask && (have & 3) == q)
-                        lds_dma16(mine + have, ring_lds + (uint32_t)((q * ring_rows + wave_u * 64) * 16));
-                }
-                if (ask) ++have;
             }
             int seen = 0;   // did any row contend in this round? (the same answer for every thread)
             if (join_passes(contend, c, tid, rho, kp, win, fill, rsub, rslot, &rows_left, more, par, true, &any[rpar], &seen)) walking = false;
             rpar ^= 1;
             if (!seen) break;
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no load into the ring is left in flight
         __syncthreads();
         if (left && rsub[lpos] != 0xFFFF) {
             sub = rsub[lpos];
@@ -801,11 +763,11 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
   }   // next tile
 }
 
-size_t pool_lds_bytes(int kp, int ring_rows)
+size_t pool_lds_bytes(int kp)
 {
-    const size_t wcnt = (size_t)PW * kp * 2, ring = (size_t)64 * ring_rows;
+    const size_t wcnt = (size_t)PW * kp * 2;   // kp >= 64, so this is at least PT entries
     return (size_t)3 * PT * 4 + (size_t)4 * kp * 4 + (size_t)3 * kp * 4 + (size_t)4 * kp * 2 + (size_t)(PT + POOL_MAX_RHO) * 2 +
-           (size_t)2 * PT * 2 + (wcnt > ring ? wcnt : ring);
+           (size_t)2 * PT * 2 + wcnt;
 }
 
 }  // namespace
@@ -814,7 +776,7 @@ hipError_t pool_launch(const PoolArgs& a, hipStream_t stream)
 {
     k_pool_meta<<<1, 1024, 0, stream>>>(a);
     if (a.n == 0) return hipGetLastError();
-    const size_t lds = pool_lds_bytes(a.kp, a.ring_rows);
+    const size_t lds = pool_lds_bytes(a.kp);
     if (lds > 60000) {
         const hipError_t e = hipFuncSetAttribute((const void*)k_pool, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
