@@ -429,6 +429,7 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
     __shared__ int rows_left;
     __shared__ int more[2];
     __shared__ int any[2];
+    __shared__ int any3[3];
     const int rho = a.rho, kp = a.kp;
     const int tid = threadIdx.x, lane = tid & 63;
     float* px = reinterpret_cast<float*>(smem);
@@ -478,7 +479,7 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
         win[k] = 0x7FFFFFFF;
         win[kp + k] = 0x7FFFFFFF;
     }
-    if (tid == 0) { more[0] = 0; more[1] = 0; any[0] = 0; any[1] = 0; }
+    if (tid == 0) { more[0] = 0; more[1] = 0; any[0] = 0; any[1] = 0; any3[0] = 0; any3[1] = 0; any3[2] = 0; }
     __syncthreads();
     {
         uint32_t o[3] = {act ? f2ord(x) : 0xFFFFFFFFu, act ? f2ord(y) : 0xFFFFFFFFu, act ? f2ord(z) : 0xFFFFFFFFu};
@@ -650,21 +651,40 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
         const uint4* mine = reinterpret_cast<const uint4*>(my_lists + (size_t)tid * pitch);
         uint4 cur = make_uint4(0, 0, 0, 0);
         if (walking) cur = mine[0];
-        int idx = 0, c = 0, rpar = 0;
+        // With rho = 2 an open sub-bucket holds one row and has room for one: whoever contends for it knows that it
+        // is closed after this round, without waiting for the winner. The contenders themselves mark it (with the
+        // round's number, so that a search of the same round still sees it open), and a round needs one barrier
+        // instead of two. stamp[c]: very negative while open, minus the round in which it closed, 1 if it was full
+        // before the rounds; open in round t means stamp[c] < 1 - t. For other rho the fill level decides (< rho).
+        const bool two = rho == 2;
+        int* stamp = reinterpret_cast<int*>(o4);   // the candidates' positions are not needed after the sort
+        if (two) {
+            for (int k = tid; k < M; k += PT) stamp[k] = fill[k] < 2 ? (int)0x80000000 : 1;
+            __syncthreads();
+        }
+        const int* level_of = two ? stamp : fill;
+        int idx = 0, c = 0, rpar = 0, r3 = 0;
         for (int round = 0; round <= PT + 1; ++round) {   // every round places at least one row; the bound is a safeguard
             bool contend = false;
-            if (tid == 0) any[rpar ^ 1] = 0;
+            const int thr = two ? 1 - round : rho;
+            if (tid == 0) {
+                if (two) any3[r3 == 2 ? 0 : r3 + 1] = 0; else any[rpar ^ 1] = 0;
+            }
             if (walking) {
                 for (;;) {   // the first sub-bucket of the sequence that still has room
                     if (idx >= nopen) break;
                     // all eight entries of the chunk are looked up together (their reads overlap, no branch per entry)
                     const unsigned int w[4] = {cur.x, cur.y, cur.z, cur.w};
                     unsigned int room = 0;
+                    int level[8];
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
                         const unsigned int eo = (j & 1) ? (w[j >> 1] >> 14) & ~3u : (w[j >> 1] << 2) & 0x3FFFCu;   // 4 * id
-                        room |= (*reinterpret_cast<const int*>(reinterpret_cast<const char*>(fill) + eo) < rho ? 1u : 0u) << j;
+                        level[j] = *reinterpret_cast<const int*>(reinterpret_cast<const char*>(level_of) + eo);
                     }
+                    __builtin_amdgcn_sched_barrier(0);   // all eight reads are under way before the first is waited for
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) room |= (level[j] < thr ? 1u : 0u) << j;
                     const int base = idx & ~7, lim = nopen - base;   // entries before idx are behind, those from nopen on are padding
                     room &= 0xFFu << (idx & 7);
                     if (lim < 8) room &= (1u << lim) - 1u;
@@ -679,16 +699,39 @@ __global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
                     if (idx < nopen) cur = mine[idx >> 3];
                 }
             }
-            if (contend) {   // first step of the passes
-                atomicMin(&win[par * kp + c], tid);
-                any[rpar] = 1;
-            }
             int seen = 0;   // did any row contend in this round? (the same answer for every thread)
-            if (join_passes(contend, c, tid, rho, kp, win, fill, rsub, rslot, &rows_left, more, par, true, &any[rpar], &seen)) walking = false;
-            rpar ^= 1;
+            if (two) {
+                if (contend) {
+                    atomicMin(&win[par * kp + c], tid);
+                    stamp[c] = -round;
+                    any3[r3] = 1;
+                }
+                lds_barrier();
+                const int w = contend ? win[par * kp + c] : -1;
+                seen = any3[r3];
+                if (contend && w == tid) {
+                    rsub[tid] = (uint16_t)c;
+                    rslot[tid] = (uint16_t)1;
+                    walking = false;
+                    win[par * kp + c] = 0x7FFFFFFF;   // next written two rounds from here, a barrier in between
+                }
+                par ^= 1;
+                r3 = r3 == 2 ? 0 : r3 + 1;
+            } else {
+                if (contend) {   // first step of the passes
+                    atomicMin(&win[par * kp + c], tid);
+                    any[rpar] = 1;
+                }
+                if (join_passes(contend, c, tid, rho, kp, win, fill, rsub, rslot, &rows_left, more, par, true, &any[rpar], &seen)) walking = false;
+                rpar ^= 1;
+            }
             if (!seen) break;
         }
         __syncthreads();
+        if (two) {   // the sub-buckets closed in the rounds are full
+            for (int k = tid; k < M; k += PT)
+                if (stamp[k] != (int)0x80000000 && stamp[k] <= 0) fill[k] = 2;
+        }
         if (left && rsub[lpos] != 0xFFFF) {
             sub = rsub[lpos];
             slot = rslot[lpos];
