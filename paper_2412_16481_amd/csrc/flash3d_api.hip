@@ -62,7 +62,7 @@ struct Plan {
     long long chunks;
     size_t bytes;
     // offsets (bytes) of the workspace arrays
-    size_t o_status, o_p0, o_c0, o_mm, o_cnt, o_cnt2, o_hist, o_key, o_left, o_leftpre, o_freepre, o_inv, o_rc, o_cfg, o_done, o_ci;
+    size_t o_status, o_p0, o_c0, o_mm, o_cnt, o_cnt2, o_hist, o_key, o_left, o_leftpre, o_freepre, o_inv, o_rc, o_cfg, o_done, o_ci, o_mmpart;
     // canonical order only
     size_t o_obox, o_owords, o_oidx0, o_oidx1, o_ohist, o_ocoords, o_operm;
     // one workgroup per scan only: the two lists of points still unplaced (index, packed voxel)
@@ -128,6 +128,7 @@ void make_plan(int64_t n, int32_t n_scans, const f3d_params* p, Plan* pl)
     pl->o_cfg = take((size_t)n_scans * 128);
     pl->o_done = take((size_t)n_scans * 4);
     pl->o_ci = take((size_t)(n / 2048 + n_scans) * 32);
+    pl->o_mmpart = take((size_t)(n / 2048 + n_scans) * 32);
     pl->o_cnt = take((size_t)(pl->max_buckets + 1) * 4);
     pl->o_cnt2 = take((size_t)(pl->max_buckets + 1) * 4);
     pl->o_freepre = take((size_t)(pl->max_buckets + 1) * 4);
@@ -261,6 +262,7 @@ static int bucketize_on(const Plan& pl, char* ws, const float* coords, const int
     a.scan_p0 = (int32_t*)(ws + pl.o_p0);
     a.scan_c0 = (int32_t*)(ws + pl.o_c0);
     a.mm = (uint32_t*)(ws + pl.o_mm);
+    a.mmpart = (uint32_t*)(ws + pl.o_mmpart);
     a.cnt = (int32_t*)(ws + pl.o_cnt);
     a.cnt_next = (int32_t*)(ws + pl.o_cnt2);
     a.hist = (int32_t*)(ws + pl.o_hist);

@@ -52,6 +52,7 @@ struct PshArgs {
     int n_chunks_ub;   // rows of chunk_info
     int32_t* done;     // [n_scans] workgroups of a scan that finished the bounding box (fast path)
     int meta_light;    // the set-up kernel leaves the bucket offsets of the scans to the caller's kernels (batch path)
+    uint32_t* mmpart;  // [chunks][8] bounding box of every chunk as ordered ints (fast path, batches of few scans)
 };
 
 hipError_t psh_launch(const PshArgs& args, hipStream_t stream);       // any size

@@ -88,6 +88,129 @@ __global__ __launch_bounds__(FTH) void k_pshf_minmax(PshArgs a)
 }
 
 // ------------------------------------------------------------------------------------------------
+// Set-up and bounding boxes in ONE launch, for batches of at most 64 scans. The scan tables (first point, first bucket,
+// first chunk of every scan) are a closed form of batch_offsets and S: every workgroup works them out itself (one
+// wave, a prefix over the scans), finds its chunk and writes the chunk's own box, without atomics, so nothing has to
+// be initialised by an earlier launch; step 0 joins the boxes of a scan's chunks. Workgroup 0 also writes the tables
+// the later kernels read.
+constexpr int SETUP_MAX_SCANS = 64;
+
+__global__ __launch_bounds__(FTH) void k_pshf_setup(PshArgs a)
+{
+    __shared__ int s_p0[SETUP_MAX_SCANS + 1], s_kb0[SETUP_MAX_SCANS + 1], s_c0[SETUP_MAX_SCANS + 1];
+    __shared__ int s_bad;
+    __shared__ uint32_t red[8];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ns = a.n_scans;
+    if (wave == 0) {
+        int p0 = 0, K = 0, c = 0;
+        bool ok = true;
+        if (lane < ns) {
+            p0 = batch_off(a, lane);
+            const int p1 = batch_off(a, lane + 1);
+            const long long nb = (long long)p1 - p0;
+            ok = nb >= 0 && nb <= a.max_scan_points && p0 >= 0 && p1 <= a.n;
+            if (lane == 0 && p0 != 0) ok = false;
+            if (lane == ns - 1 && p1 != a.n) ok = false;
+            if (ok) {
+                K = (int)((nb + a.S - 1) / a.S);
+                c = (int)((nb + FCH - 1) / FCH);
+            }
+        }
+        const bool bad = __builtin_amdgcn_ballot_w64(!ok) != 0ull;
+        const int kin = wave_incl_scan(K, lane), cin = wave_incl_scan(c, lane);
+        if (lane < ns) {
+            s_p0[lane] = p0;
+            s_kb0[lane] = kin - K;
+            s_c0[lane] = cin - c;
+        }
+        if (lane == ns - 1) {
+            s_p0[ns] = a.n;
+            s_kb0[ns] = kin;
+            s_c0[ns] = cin;
+        }
+        if (lane == 0) s_bad = bad ? 1 : 0;
+    }
+    __syncthreads();
+    const int isbad = s_bad, ktot = s_kb0[ns], ctot = s_c0[ns];
+    if (blockIdx.x == 0) {   // the tables of the later kernels
+        if (tid < ns) {
+            a.sbs[tid] = s_kb0[tid];
+            a.scan_c0[tid] = s_c0[tid];
+            a.scan_p0[tid] = s_p0[tid];
+            a.done[tid] = 0;
+        }
+        if (tid == 0) {
+            a.sbs[ns] = isbad ? -1 : ktot;
+            a.scan_c0[ns] = isbad ? 0 : ctot;
+            a.scan_p0[ns] = a.n;
+            a.status[0] = isbad;
+        }
+        if (tid < 8) a.round_count[tid] = 0;
+        if (!isbad) {
+            // first row of every bucket (buckets are full except the last of a scan); a wave takes a scan
+            for (int b = wave; b < ns; b += FW) {
+                const int p0 = s_p0[b], nb = s_p0[b + 1] - p0, kb0 = s_kb0[b], K = s_kb0[b + 1] - kb0;
+                for (int j = lane; j < K; j += 64) {
+                    a.offsets[kb0 + j] = p0 + min(j * a.S, nb);
+                    a.cnt[kb0 + j] = 0;
+                }
+            }
+            for (int j = ktot + tid; j <= a.max_buckets; j += FTH) a.offsets[j] = a.n;
+        }
+    }
+    const int chunk = blockIdx.x;
+    if (isbad || chunk >= ctot) {
+        if (tid == 0) a.chunk_info[2 * chunk] = make_int4(-1, 0, 0, 0);
+        return;
+    }
+    // the chunk's scan: the last one that starts at or before it (scans without points have no chunks)
+    const int b = __popcll(__builtin_amdgcn_ballot_w64(lane < ns && s_c0[lane] <= chunk)) - 1;
+    const int p0 = s_p0[b], p1 = s_p0[b + 1], c0 = s_c0[b], lc = chunk - c0;
+    const int begin = p0 + lc * FCH, end = min(begin + FCH, p1);
+    if (tid == 0) {
+        a.chunk_info[2 * chunk] = make_int4(b, lc, s_c0[b + 1] - c0, begin);
+        a.chunk_info[2 * chunk + 1] = make_int4(end, s_kb0[b], s_kb0[b + 1] - s_kb0[b], c0);
+    }
+    uint32_t mn[3] = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu}, mx[3] = {0u, 0u, 0u};
+    const float* src = a.coords + (size_t)begin * 3;
+    const int nf = (end - begin) * 3;
+    float v[3 * FPPT];
+#pragma unroll
+    for (int j = 0; j < 3 * FPPT; ++j) {   // all twelve loads in flight together
+        const int f = tid + j * FTH;
+        v[j] = f < nf ? src[f] : 0.f;
+    }
+#pragma unroll
+    for (int j = 0; j < 3 * FPPT; ++j) {
+        const int f = tid + j * FTH;
+        if (f < nf) {
+            const uint32_t o = f2ord(v[j]);
+            const int ax = f % 3;
+#pragma unroll
+            for (int t = 0; t < 3; ++t)
+                if (ax == t) { mn[t] = min(mn[t], o); mx[t] = max(mx[t], o); }
+        }
+    }
+    if (tid < 3) { red[tid] = 0xFFFFFFFFu; red[4 + tid] = 0u; }
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < 3; ++t) {
+        uint32_t lo = mn[t], hi = mx[t];
+        for (int d = 32; d >= 1; d >>= 1) {
+            lo = min(lo, (uint32_t)__shfl_xor((int)lo, d, 64));
+            hi = max(hi, (uint32_t)__shfl_xor((int)hi, d, 64));
+        }
+        if (lane == 0) { atomicMin(&red[t], lo); atomicMax(&red[4 + t], hi); }
+    }
+    __syncthreads();
+    if (tid < 3) {
+        a.mmpart[chunk * 8 + tid] = red[tid];
+        a.mmpart[chunk * 8 + 4 + tid] = red[4 + tid];
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // step r: settle step r-1 from the count rows of that step, then rank the contenders of step r
 // dynamic LDS: tot[kcap] + pre[kcap] ints + NW x kwp words of packed 16-bit counters.
 // TH threads rank the 2048 points of a chunk: 512 (four points each, two workgroups per CU) when the grid is
@@ -115,8 +238,27 @@ __global__ __launch_bounds__(TH) void k_pshf_step(PshArgs a, int r, const uint32
     uint32_t box[8];
     uint32_t cfgw = 0;
     if (r == 0) {
-        if (tid == 0)
+        if (a.mmpart) {   // the boxes of the scan's chunks, joined by the first wave
+            if (wave == 0) {
+                uint32_t lo[3] = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu}, hi[3] = {0u, 0u, 0u};
+                for (int t = lane; t < ci.nc; t += 64) {
+                    const uint32_t* pb = a.mmpart + (size_t)(ci.c0 + t) * 8;
+#pragma unroll
+                    for (int ax = 0; ax < 3; ++ax) { lo[ax] = min(lo[ax], pb[ax]); hi[ax] = max(hi[ax], pb[4 + ax]); }
+                }
+#pragma unroll
+                for (int ax = 0; ax < 3; ++ax) {
+                    for (int d = 32; d >= 1; d >>= 1) {
+                        lo[ax] = min(lo[ax], (uint32_t)__shfl_xor((int)lo[ax], d, 64));
+                        hi[ax] = max(hi[ax], (uint32_t)__shfl_xor((int)hi[ax], d, 64));
+                    }
+                    box[ax] = lo[ax];
+                    box[4 + ax] = hi[ax];
+                }
+            }
+        } else if (tid == 0) {
             for (int i = 0; i < 8; ++i) box[i] = a.mm[ci.b * 8 + i];
+        }
     } else if (tid < CFGW) {
         cfgw = reinterpret_cast<const uint32_t*>(reinterpret_cast<const ScanCfg*>(a.cfg) + ci.b)[tid];
     }
@@ -412,9 +554,14 @@ hipError_t psh_fast_launch(const PshArgs& args, hipStream_t stream)
     a.chunk = FCH;
     const int chunks = (int)(a.n / FCH) + a.n_scans;  // upper bound, surplus workgroups exit
     a.n_chunks_ub = chunks;
-    k_psh_meta<<<1, 1024, 0, stream>>>(a);
-    if (a.n == 0) return hipGetLastError();
-    k_pshf_minmax<<<chunks, FTH, 0, stream>>>(a);
+    if (a.n_scans <= SETUP_MAX_SCANS && a.n > 0) {
+        k_pshf_setup<<<chunks, FTH, 0, stream>>>(a);
+    } else {
+        a.mmpart = nullptr;
+        k_psh_meta<<<1, 1024, 0, stream>>>(a);
+        if (a.n == 0) return hipGetLastError();
+        k_pshf_minmax<<<chunks, FTH, 0, stream>>>(a);
+    }
     const int kwp = row_pitch(a.kcap);
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
