@@ -350,7 +350,8 @@ __device__ __forceinline__ void sort_choices(int nleft, int nopen, int pitch, co
 }
 
 // Workgroup barrier for steps that exchange data through LDS only: waits for this wave's LDS operations, not for
-// its global loads (__syncthreads() waits for both, and the rounds below keep a list prefetch in flight).
+// its global loads (__syncthreads() waits for both; in the rounds below the read of a row's next list chunk may still
+// be in flight at the barrier, and is waited for where the chunk is used).
 __device__ __forceinline__ void lds_barrier()
 {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
