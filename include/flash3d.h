@@ -299,8 +299,8 @@ int f3d_ln_linear(const void *x, const int32_t *row_in, const float *gamma, cons
  *   pooled_offsets (out) [n_scans+1] first pooled row of every scan; last entry = number of pooled rows, or -1
  *                       if batch_offsets was inconsistent (then nothing else is written)
  *   workspace           >= f3d_pool_workspace_bytes(), 256-byte aligned: the tile table, a tile counter, and for
- *                       each of up to 256 resident workgroups the sorted choice lists of its tile's leftover rows
- *                       ((tile/2 + 8)^2 two-byte entries: 0.53 MB at tile 1024, 138 MB in all for large inputs)
+ *                       each of up to 512 resident workgroups the sorted choice lists of its tile's leftover rows
+ *                       ((tile/2 + 8)^2 two-byte entries: 0.53 MB at tile 1024, 277 MB in all for large inputs)
  */
 #define F3D_POOL_SUM 0
 #define F3D_POOL_MEAN 1

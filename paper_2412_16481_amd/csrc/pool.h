@@ -7,7 +7,7 @@ namespace f3d {
 
 constexpr int POOL_MAX_TILE = 1024;   // rows of a tile = threads of a workgroup
 constexpr int POOL_MAX_RHO = 64;
-constexpr int POOL_MAX_SLOTS = 256;   // resident workgroups: one per compute unit (1024 threads at up to 128 registers fill its register files)
+constexpr int POOL_MAX_SLOTS = 512;   // resident workgroups: at most two per compute unit
 
 // Entries (16-bit ids) of one workgroup's choice lists: rows left x open sub-buckets rounded up to 8. With n rows and
 // M sub-buckets at most n - M rows are left and at most M sub-buckets are open: (n - M)(M + 7) <= (n / 2 + 4)^2.

@@ -420,7 +420,12 @@ __device__ __forceinline__ bool join_passes(bool contend, int c, int tid, int rh
 //
 // Workgroups are persistent: each takes tiles from a counter until none is left, and owns one slot of the
 // choice-list area in global memory (its block index).
-__global__ __launch_bounds__(PT) void k_pool(PoolArgs a)
+// WPE = waves per SIMD the kernel is compiled for: 4 (128 registers, one workgroup per compute unit) or 8 (64
+// registers, a little spilling in the sort, two workgroups per compute unit). A tile's rounds leave the vector ALU
+// idle most of the time and its sort saturates it: with two workgroups resident, one's rounds run beside the other's
+// sort. With no more tiles than compute units there is nothing to put beside, and the form without spills is taken.
+template <int WPE>
+__global__ __launch_bounds__(PT, WPE) void k_pool(PoolArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __shared__ int lds[17];
@@ -821,11 +826,21 @@ hipError_t pool_launch(const PoolArgs& a, hipStream_t stream)
     k_pool_meta<<<1, 1024, 0, stream>>>(a);
     if (a.n == 0) return hipGetLastError();
     const size_t lds = pool_lds_bytes(a.kp);
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
+    const bool two = cus > 0 && a.n_tiles_ub > cus && 2 * lds <= 160 * 1024;
     if (lds > 60000) {
-        const hipError_t e = hipFuncSetAttribute((const void*)k_pool, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        const hipError_t e = two ? hipFuncSetAttribute((const void*)k_pool<8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
+                                 : hipFuncSetAttribute((const void*)k_pool<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    k_pool<<<a.n_slots, PT, lds, stream>>>(a);
+    if (two) {
+        const int grid = a.n_slots < 2 * cus ? a.n_slots : 2 * cus;
+        k_pool<8><<<grid, PT, lds, stream>>>(a);
+    } else {
+        const int grid = cus > 0 && a.n_slots > cus ? cus : a.n_slots;
+        k_pool<4><<<grid, PT, lds, stream>>>(a);
+    }
     return hipGetLastError();
 }
 
