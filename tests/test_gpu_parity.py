@@ -1016,6 +1016,21 @@ def test_pool_matches_oracle_on_the_largest_lidar_layout(rho, op):
         assert ref["step_of"].max() >= 300
 
 
+@pytest.mark.timeout(600)
+def test_pool_more_tiles_than_compute_units_other_shapes():
+    """More tiles than the GPU has compute units: the form of the kernel with two workgroups per compute unit, on
+    tiles of 512 and 1000 rows, other capacities, hashes and reductions than the LiDAR test above, clustered input."""
+    rng = np.random.default_rng(48)
+    n = 330_000
+    c = (rng.normal(size=(n, 3)) * 0.02 + rng.integers(0, 40, (n, 1)) * 1.5).astype(np.float32)   # 40 tight clusters on a line
+    c[::5] = (rng.random((len(c[::5]), 3)) * 60).astype(np.float32)
+    bo = np.array([0, 100_000, 100_000, 215_321, n], dtype=np.int32)
+    feat = wl.f32_to_bf16_bits(rng.standard_normal((n, 8)).astype(np.float32))
+    check_pool(c, None, feat, bo, 512, 3, 0.25, "xor_mod", "sum")
+    check_pool(c, None, feat, bo, 1000, 2, 0.1, "zorder_mod", "min")
+    check_pool(c, None, feat, bo, 1024, 16, 0.5, "xor_div", "mean")
+
+
 def test_pool_on_scans_with_ragged_tiles_and_bucket_major_coordinates():
     rng = np.random.default_rng(41)
     sizes = [1, 1023, 1024, 1025, 0, 3000, 77, 0, 5]
