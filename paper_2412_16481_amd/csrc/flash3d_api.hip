@@ -94,8 +94,9 @@ int check_params(int64_t n, int32_t n_scans, const f3d_params* p)
 }
 
 // One workgroup per scan pays when the scans themselves fill the GPU. Measured on an MI355X: that path needs about
-// 10.4 ns per point of the LARGEST scan and per round of 256 scans (a workgroup walks its scan alone), the paths that
-// spread a scan over the GPU about 0.13 ms plus 0.125 ns per point of the whole batch.
+// 10.4 ns per point of the LARGEST scan and per round of 256 scans (a workgroup walks its scan alone; with more scans
+// than compute units two workgroups share one and a round is about 15 % shorter than this), the paths that spread a
+// scan over the GPU about 0.13 ms plus 0.125 ns per point of the whole batch.
 bool wants_scans(int64_t n, int32_t n_scans, const f3d_params* p, long long max_scan_points, int kcap)
 {
     if (!f3d::psh_scan_eligible(kcap)) return false;

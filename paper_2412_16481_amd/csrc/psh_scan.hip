@@ -34,8 +34,11 @@ __device__ __forceinline__ unsigned long long pack_voxel(int x, int y, int z)
 // dynamic LDS, in 32-bit words: fill[K] run[2][K] wh[SNW][kw] wbase[SNW][kw] with kw = (K + 1) / 2.
 // The hash function is a template parameter: the kernel holds many scan-wide values in scalar registers, and the
 // branches between four hash functions cost enough of them to spill.
-template <int HASH>
-__global__ __launch_bounds__(STH) void k_pshs_scan(PshArgs a, int32_t* __restrict__ lidx0, int32_t* __restrict__ lidx1,
+// WPE = waves per SIMD the kernel is compiled for: 4 (128 registers, one workgroup per compute unit) or 8 (64
+// registers at the price of a few spills, two workgroups per compute unit: taken when there are more scans than
+// compute units, where the second workgroup fills the issue slots the first leaves at its barriers).
+template <int HASH, int WPE>
+__global__ __launch_bounds__(STH, WPE) void k_pshs_scan(PshArgs a, int32_t* __restrict__ lidx0, int32_t* __restrict__ lidx1,
                                                    unsigned long long* __restrict__ lvox0, unsigned long long* __restrict__ lvox1)
 {
     extern __shared__ int smem[];
@@ -367,17 +370,26 @@ hipError_t psh_scan_launch(const PshArgs& args, int32_t* lidx0, int32_t* lidx1, 
     if (a.n == 0) return hipGetLastError();
     const size_t kw = (size_t)(a.kcap + 1) / 2;
     const size_t lds = ((size_t)3 * a.kcap + 2 * SNW * kw) * 4;
-    const void* fn[4] = {(const void*)k_pshs_scan<0>, (const void*)k_pshs_scan<1>, (const void*)k_pshs_scan<2>,
-                         (const void*)k_pshs_scan<3>};
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
+    const bool two = cus > 0 && a.n_scans > cus && 2 * lds <= 150 * 1024;
+    const void* fn[8] = {(const void*)k_pshs_scan<0, 4>, (const void*)k_pshs_scan<1, 4>, (const void*)k_pshs_scan<2, 4>,
+                         (const void*)k_pshs_scan<3, 4>, (const void*)k_pshs_scan<0, 8>, (const void*)k_pshs_scan<1, 8>,
+                         (const void*)k_pshs_scan<2, 8>, (const void*)k_pshs_scan<3, 8>};
+    const int which = (a.hash & 3) + (two ? 4 : 0);
     if (lds > 60000) {
-        const hipError_t e = hipFuncSetAttribute(fn[a.hash & 3], hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        const hipError_t e = hipFuncSetAttribute(fn[which], hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    switch (a.hash) {
-        case 0: k_pshs_scan<0><<<a.n_scans, STH, lds, stream>>>(a, lidx0, lidx1, lvox0, lvox1); break;
-        case 1: k_pshs_scan<1><<<a.n_scans, STH, lds, stream>>>(a, lidx0, lidx1, lvox0, lvox1); break;
-        case 2: k_pshs_scan<2><<<a.n_scans, STH, lds, stream>>>(a, lidx0, lidx1, lvox0, lvox1); break;
-        default: k_pshs_scan<3><<<a.n_scans, STH, lds, stream>>>(a, lidx0, lidx1, lvox0, lvox1); break;
+    switch (which) {
+        case 0: k_pshs_scan<0, 4><<<a.n_scans, STH, lds, stream>>>(a, lidx0, lidx1, lvox0, lvox1); break;
+        case 1: k_pshs_scan<1, 4><<<a.n_scans, STH, lds, stream>>>(a, lidx0, lidx1, lvox0, lvox1); break;
+        case 2: k_pshs_scan<2, 4><<<a.n_scans, STH, lds, stream>>>(a, lidx0, lidx1, lvox0, lvox1); break;
+        case 3: k_pshs_scan<3, 4><<<a.n_scans, STH, lds, stream>>>(a, lidx0, lidx1, lvox0, lvox1); break;
+        case 4: k_pshs_scan<0, 8><<<a.n_scans, STH, lds, stream>>>(a, lidx0, lidx1, lvox0, lvox1); break;
+        case 5: k_pshs_scan<1, 8><<<a.n_scans, STH, lds, stream>>>(a, lidx0, lidx1, lvox0, lvox1); break;
+        case 6: k_pshs_scan<2, 8><<<a.n_scans, STH, lds, stream>>>(a, lidx0, lidx1, lvox0, lvox1); break;
+        default: k_pshs_scan<3, 8><<<a.n_scans, STH, lds, stream>>>(a, lidx0, lidx1, lvox0, lvox1); break;
     }
     return hipGetLastError();
 }

@@ -115,6 +115,22 @@ def test_bucketize_batches_of_many_scans_take_the_scan_path_by_themselves():
     check_bucketize(c, bo, 0.05, 256, 4, "xor_div", max_scan_points=largest, order="canonical")
 
 
+@pytest.mark.parametrize("hash", HASHES)
+def test_bucketize_more_scans_than_compute_units(hash):
+    """300 uneven scans: more workgroups than the GPU has compute units, which takes the form of the one-workgroup-
+    per-scan kernel that is compiled for two workgroups per compute unit."""
+    rng = np.random.default_rng(311 + HASHES.index(hash))
+    sizes = rng.integers(0, 2500, 300)
+    sizes[[0, 17, 299]] = 0
+    sizes[5] = 9000
+    bo = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    n = int(bo[-1])
+    c = np.concatenate([clustered_cloud(rng, int(sz), 1.5 * i) for i, sz in enumerate(sizes)]).astype(np.float32).reshape(n, 3)
+    largest = int(sizes.max())
+    check_bucketize(c, bo, 0.05, 256, 4, hash, max_scan_points=largest, schedule="scans")
+    check_bucketize(c, bo, 0.05, 128, 2, hash, n_probes=3, max_scan_points=largest, schedule="scans")
+
+
 def test_bucketize_one_workgroup_per_scan_is_refused_above_1024_buckets_per_scan():
     p = f3d.make_params(0.05, 64, 4, "zorder_div", schedule="scans")      # S = 16: 20000 points are 1250 buckets
     with pytest.raises(f3d.Flash3DError) as e:
